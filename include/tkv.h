@@ -1,0 +1,221 @@
+/*
+ * tkv.h -- C ABI of libtkv: TriAxialKV's decode / append hot path on AMD
+ * MI355X (gfx950).
+ *
+ * The library quantises newly written bf16 keys / values at a per-token
+ * bitwidth (INT2 or INT4, chosen upstream from the token's temporal x
+ * modality x semantic-role tag) into a paged mixed-precision KV pool, and
+ * runs decode attention over that pool with on-the-fly dequantisation.
+ *
+ * Conventions
+ *  - Every function returns an int status (TKV_OK = 0, errors negative)
+ *    unless its type says otherwise; nothing throws, aborts or prints.
+ *  - "host" pointers are ordinary CPU memory; "device" pointers are HIP
+ *    device memory on the current device.  The caller owns every buffer and
+ *    the stream.  The library allocates no device memory, never synchronises
+ *    a stream and keeps no global state: calls on different streams are
+ *    independent.
+ *  - Argument checks that are possible from host-visible values are done
+ *    before anything is launched, so a bad call launches nothing.
+ *  - Geometry is fixed in this version: head_dim 128, group_size 32,
+ *    page_tokens 64; other values return TKV_ERR_BAD_SHAPE.
+ *  - bf16 and fp16 values are raw 16-bit patterns.
+ */
+#ifndef TKV_H
+#define TKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TKV_OK = 0,
+    TKV_ERR_INVALID_ARG = -1,        /* null pointer, negative count, misaligned buffer */
+    TKV_ERR_BAD_BITS = -2,           /* a bitwidth other than 2 or 4                      */
+    TKV_ERR_BAD_SHAPE = -3,          /* unsupported geometry / head counts                */
+    TKV_ERR_PAGE_RANGE = -4,         /* page id outside its pool                          */
+    TKV_ERR_POOL_EXHAUSTED = -5,     /* allocator has too few free pages (state unchanged) */
+    TKV_ERR_WORKSPACE_TOO_SMALL = -6,
+    TKV_ERR_HIP = -7,                /* a launch failed; see hipGetLastError               */
+    TKV_ERR_CAPACITY = -8            /* an output array supplied by the caller is too small */
+};
+
+/* Bits the kernels may OR into the optional device status word. */
+enum {
+    TKV_STATUS_TAG_MISMATCH = 1,     /* append: tag_bits[token] differs from its page's pool width (token skipped) */
+    TKV_STATUS_BITMAP_MISMATCH = 2,  /* decode: bit_map[page] differs from the width its position implies (page skipped) */
+    TKV_STATUS_PAGE_RANGE = 4        /* a page id read on the device lies outside the pool (page skipped) */
+};
+
+const char *tkv_strerror(int status);
+
+/*
+ * Pool geometry.  Pages [0, n_pages_int2) form the INT2 pool, pages
+ * [n_pages_int2, n_pages_int2 + n_pages_int4) the INT4 pool: one address
+ * space split by an offset, so a page's precision is one comparison
+ * (paper Sec. 3.2.2, "Shared address space").
+ */
+typedef struct tkv_desc {
+    int32_t n_kv_heads;
+    int32_t head_dim;       /* 128 */
+    int32_t group_size;     /* 32  */
+    int32_t page_tokens;    /* 64  */
+    int32_t n_pages_int2;
+    int32_t n_pages_int4;
+} tkv_desc;
+
+/* Bytes of one (page, kv head) record: 6144 for bits = 2, 10240 for bits = 4, 0 otherwise
+ * (codes of K and V plus fp16 scale and zero-point per group of 32 channels, Sec. 3.2.1). */
+size_t tkv_record_bytes(int bits);
+/* Bytes of one page (all kv heads), or 0 on a bad descriptor / width. */
+size_t tkv_page_bytes(const tkv_desc *desc, int bits);
+/* Bytes of the whole pool; the caller allocates this much device memory, 256-byte aligned. */
+size_t tkv_pool_bytes(const tkv_desc *desc);
+/* Byte offset of the record of (page, head) inside the pool, or (size_t)-1 if out of range. */
+size_t tkv_record_offset(const tkv_desc *desc, int32_t page, int32_t head);
+
+/* ------------------------------------------------------------------ */
+/* Page allocators (host).  One free list per pool, no coordination     */
+/* between them (Sec. 3.2.2, "Memory allocation").                      */
+/* ------------------------------------------------------------------ */
+typedef struct tkv_alloc tkv_alloc;
+
+/* shuffle_seed = 0: pages are handed out in increasing order; otherwise each
+ * free list is shuffled with a generator seeded by it (scattered pages). */
+int tkv_alloc_create(const tkv_desc *desc, uint64_t shuffle_seed, tkv_alloc **out);
+void tkv_alloc_destroy(tkv_alloc *a);
+/* Take n free pages of the given width into page_ids_out (host, n entries).
+ * On TKV_ERR_POOL_EXHAUSTED nothing is taken. */
+int tkv_alloc_pages(tkv_alloc *a, int bits, int32_t n, int32_t *page_ids_out);
+/* Return pages to their pools (width follows from the id).  A page that is
+ * out of range or already free gives TKV_ERR_PAGE_RANGE and nothing is freed. */
+int tkv_free_pages(tkv_alloc *a, const int32_t *page_ids, int32_t n);
+int32_t tkv_alloc_free_count(const tkv_alloc *a, int bits);
+
+/* ------------------------------------------------------------------ */
+/* Per-sequence page table (host).  A sequence owns two page streams:   */
+/* its INT2 tokens fill INT2 pages in arrival order, its INT4 tokens    */
+/* INT4 pages.  Listing INT2 pages before INT4 pages is the partition   */
+/* that lets decode run width-homogeneous work (Sec. 3.2.3, "Decode",   */
+/* phase 1).                                                            */
+/* ------------------------------------------------------------------ */
+typedef struct tkv_seq tkv_seq;
+
+int tkv_seq_create(tkv_seq **out);
+void tkv_seq_destroy(tkv_seq *s);                      /* does not return pages */
+int tkv_seq_release(tkv_seq *s, tkv_alloc *a);         /* returns every page, empties the sequence */
+int32_t tkv_seq_n_tokens(const tkv_seq *s, int bits);  /* tokens stored at this width */
+int32_t tkv_seq_n_pages(const tkv_seq *s, int bits);
+/* Copy the page list, INT2 pages first then INT4 pages, into out (host,
+ * capacity entries).  Returns the number of pages or TKV_ERR_CAPACITY. */
+int32_t tkv_seq_page_ids(const tkv_seq *s, int32_t *out, int32_t capacity);
+
+/* ------------------------------------------------------------------ */
+/* Q1: route newly arrived tokens to slots (host).                      */
+/* ------------------------------------------------------------------ */
+/* Upper bound of pages one tkv_plan_append call over n_tokens can touch. */
+int32_t tkv_plan_append_max_work(int32_t n_tokens);
+/*
+ * tag_bits (host, u8[n_tokens]) is the per-token bitwidth array produced by
+ * the tagger and the tag -> bitwidth table (Sec. 3.2.3, "Tagging").  Tokens
+ * of each width are appended, in order, to the sequence's page stream of that
+ * width; new pages come from the matching allocator.  Outputs (host):
+ *   slot_ids_out[n_tokens]      page_id * 64 + slot of every token (the
+ *                               per-token pointer of the page table);
+ *   work_pages_out[max_work]    the distinct pages that receive tokens;
+ *   work_src_out[max_work*64]   for each such page and slot, token_base +
+ *                               index of the token that goes there, or -1;
+ *   *n_work_out                 number of pages listed.
+ * token_base lets several sequences' plans address one concatenated K/V
+ * tensor.  On any error the sequence and the allocator are left unchanged.
+ */
+int tkv_plan_append(tkv_alloc *a, tkv_seq *s, const uint8_t *tag_bits, int32_t n_tokens,
+                    int32_t token_base, int32_t *slot_ids_out, int32_t *work_pages_out,
+                    int32_t *work_src_out, int32_t max_work, int32_t *n_work_out);
+
+/* ------------------------------------------------------------------ */
+/* Q2-Q5: quantise and pack (device).                                   */
+/* ------------------------------------------------------------------ */
+/*
+ * For every listed page and kv head: asymmetric min/max quantisation of each
+ * group of 32 channels of each arriving token (zero = fp16(min), scale =
+ * fp16((max-min)/(2^b-1)), code = round-half-even((x-zero)*(1/scale)) clamped),
+ * per-token for K and V at both widths (Sec. 3.2.1), packed into the page's
+ * planes; bit_map[page] is set to the page's width.  Bits of slots whose
+ * work_src entry is -1 are left untouched.
+ *   pool       device, tkv_pool_bytes(desc) bytes, 256-byte aligned
+ *   bit_map    device u8[n_pages_int2 + n_pages_int4]
+ *   K, V       device bf16 [n_tokens, n_kv_heads, head_dim], contiguous
+ *   tag_bits   device u8[n_tokens]; a token whose width differs from its
+ *              page's pool is skipped and TKV_STATUS_TAG_MISMATCH is raised
+ *   work_pages device i32[n_work], work_src device i32[n_work*64] as written
+ *              by tkv_plan_append; a page may appear at most once per call
+ *   status     device i32, may be NULL; kernels OR TKV_STATUS_* bits into it
+ * group_size must be 32.  n_work = 0 is a no-op.
+ */
+int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
+                        const void *K, const void *V, const uint8_t *tag_bits,
+                        int32_t n_tokens, int32_t group_size,
+                        const int32_t *work_pages, const int32_t *work_src, int32_t n_work,
+                        int32_t *status, void *stream /* hipStream_t */);
+
+/* ------------------------------------------------------------------ */
+/* D1: cut page lists into work items (host).                           */
+/* ------------------------------------------------------------------ */
+/*
+ * The decode kernel follows the flash-decoding design: the KV of a sequence
+ * is processed as parallel contiguous splits merged by log-sum-exp
+ * (Sec. 3.2.3, "Decode").  A work item is a contiguous range of one
+ * sequence's page list (INT2 pages first).  Items are balanced by bytes: an
+ * INT2 page weighs 3, an INT4 page 5.
+ *   page_indptr   host i32[batch+1], page-list offsets of the sequences
+ *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial)
+ *   target_items  wanted number of items over the whole batch (>= 1)
+ *   items_out     host i32[4*capacity]: {sequence, first page, end page, 0},
+ *                 page indices relative to the sequence's list
+ *   seq_item_indptr_out  host i32[batch+1]: items of sequence b are
+ *                 [indptr[b], indptr[b+1]); a sequence without tokens has none
+ * Returns the number of items (>= 0) or a negative status.
+ */
+int32_t tkv_plan_decode_capacity(int32_t batch, int32_t target_items);
+int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page_indptr,
+                        const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                        int32_t target_items, int32_t *items_out, int32_t capacity,
+                        int32_t *seq_item_indptr_out);
+
+/* ------------------------------------------------------------------ */
+/* D2-D7: decode attention (device).                                    */
+/* ------------------------------------------------------------------ */
+/* Bytes of workspace for n_items items: fp32 (m, l, acc[head_dim]) per item and query head. */
+size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t n_q_heads);
+/*
+ * out[b, h, :] = softmax(sm_scale * q[b, h, :] . K^T) V over the dequantised
+ * tokens of sequence b's pages, query head h reading kv head
+ * h / (n_q_heads / n_kv_heads).  A sequence with no tokens gives zeros.
+ *   pool, bit_map  device, as filled by tkv_quantize_append
+ *   q              device bf16 [batch, n_q_heads, head_dim]
+ *   page_indptr    device i32[batch+1]
+ *   page_ids       device i32[page_indptr[batch]]: per sequence INT2 pages then INT4 pages
+ *   n_tok_int2/4   device i32[batch]
+ *   items          device i32[4*n_items], seq_item_indptr device i32[batch+1] (tkv_plan_decode)
+ *   out            device fp32 [batch, n_q_heads, head_dim]
+ *   workspace      device, >= tkv_decode_workspace_bytes(...), 16-byte aligned
+ *   status         device i32, may be NULL
+ * n_q_heads / n_kv_heads must be 1, 2, 4 or 8.  Two launches on `stream`:
+ * the split kernel, then the cross-split reduction.
+ */
+int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                         const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                         const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                         const int32_t *items, const int32_t *seq_item_indptr, int32_t n_items,
+                         int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
+                         void *workspace, size_t workspace_bytes, int32_t *status,
+                         void *stream /* hipStream_t */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TKV_H */

@@ -1,0 +1,182 @@
+// tkv_quantize_append: quantise newly written bf16 K/V at a per-token width
+// (INT2 / INT4) and pack codes, fp16 scales and fp16 zero-points into the
+// paged pool (paper Sec. 3.2.1 for the quantisation scheme, Sec. 3.2.2-3.2.3
+// for the two pools and the per-token bitwidth array).
+//
+// One workgroup of 256 threads owns one (destination page, kv head) record.
+// Thread (slot = tid/4, group = tid%4) quantises one group of 32 channels of
+// the token bound for that slot, for K and for V, entirely in registers: a
+// group is 64 contiguous bytes of the input, so min/max need no cross-lane
+// step.  K words go straight to HBM (a wavefront's stores for one word index
+// are 256 contiguous bytes).  V codes are transposed through LDS, because
+// the V plane packs tokens, not channels, into a word.
+//
+// Arithmetic is IEEE binary32 without fused multiply-add so that the codes,
+// scales and zero-points match a scalar CPU evaluation bit for bit:
+//   zero = fp16(min), scale = fp16((max - min) / (2^b - 1)),
+//   code = clamp(rint((x - zero) * (1 / scale)), 0, 2^b - 1), 0 if scale == 0.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "tkv_internal.h"
+#include "tkv_layout.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+using namespace tkv;
+
+struct GroupQ {
+    uint32_t words[4];   // packed codes: INT4 uses 4 words (8 channels each), INT2 2 words (16 each)
+    uint32_t bytes[8];   // the same 32 codes, one per byte (for the V transpose)
+    uint16_t scale, zero;
+};
+
+template <int BITS>
+__device__ __forceinline__ GroupQ quantize_group(const uint4 *src)
+{
+    constexpr int L = (1 << BITS) - 1;
+    float f[32];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 v = src[i];
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[8 * i + 2 * k] = __uint_as_float(u[k] << 16);
+            f[8 * i + 2 * k + 1] = __uint_as_float(u[k] & 0xffff0000u);
+        }
+    }
+    float mn = f[0], mx = f[0];
+#pragma unroll
+    for (int i = 1; i < 32; ++i) {
+        mn = f[i] < mn ? f[i] : mn;
+        mx = f[i] > mx ? f[i] : mx;
+    }
+    if (mn == 0.0f) mn = 0.0f;   // -0 -> +0
+    const float r = __fsub_rn(mx, mn);
+    const float s32 = __fdiv_rn(r, (float)L);
+    const __half sh = __float2half_rn(s32), zh = __float2half_rn(mn);
+    const float s = __half2float(sh), z = __half2float(zh);
+    GroupQ out;
+    out.scale = __half_as_ushort(sh);
+    out.zero = __half_as_ushort(zh);
+    const float inv = s == 0.0f ? 0.0f : __fdiv_rn(1.0f, s);
+    uint32_t c[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        float t = rintf(__fmul_rn(__fsub_rn(f[i], z), inv));
+        t = fminf(fmaxf(t, 0.0f), (float)L);
+        c[i] = s == 0.0f ? 0u : (uint32_t)(int)t;
+    }
+#pragma unroll
+    for (int w = 0; w < 4; ++w) out.words[w] = 0;
+    constexpr int per_word = 32 / BITS;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) out.words[i / per_word] |= c[i] << (BITS * (i % per_word));
+#pragma unroll
+    for (int w = 0; w < 8; ++w)
+        out.bytes[w] = c[4 * w] | (c[4 * w + 1] << 8) | (c[4 * w + 2] << 16) | (c[4 * w + 3] << 24);
+    return out;
+}
+
+template <int BITS>
+__device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, const uint16_t *V, int src,
+                                              bool valid, int head, int n_kv_heads,
+                                              uint32_t (*lds_codes)[32], uint8_t *lds_valid)
+{
+    using R = Rec<BITS>;
+    const int tid = threadIdx.x, slot = tid >> 2, g = tid & 3;
+    const int tile = slot >> 4, row = slot & 15;
+    if (g == 0) lds_valid[slot] = valid;
+    if (valid) {
+        const size_t e = ((size_t)src * n_kv_heads + head) * kHeadDim + g * kGroup;
+        const GroupQ kq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(K + e));
+        uint32_t *kc = reinterpret_cast<uint32_t *>(rec + R::kKCodes);
+        constexpr int words = BITS;   // 32-bit words of codes per group: 4 (INT4) or 2 (INT2)
+#pragma unroll
+        for (int w = 0; w < words; ++w) kc[((tile * words + w) * 16 + row) * 4 + g] = kq.words[w];
+        reinterpret_cast<uint16_t *>(rec + R::kKScale)[slot * 4 + g] = kq.scale;
+        reinterpret_cast<uint16_t *>(rec + R::kKZero)[slot * 4 + g] = kq.zero;
+
+        const GroupQ vq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(V + e));
+        const int mi = vmeta_index(slot, g);
+        reinterpret_cast<uint16_t *>(rec + R::kVScale)[mi] = vq.scale;
+        reinterpret_cast<uint16_t *>(rec + R::kVZero)[mi] = vq.zero;
+        uint4 *dst = reinterpret_cast<uint4 *>(&lds_codes[slot][g * 8]);
+        dst[0] = make_uint4(vq.bytes[0], vq.bytes[1], vq.bytes[2], vq.bytes[3]);
+        dst[1] = make_uint4(vq.bytes[4], vq.bytes[5], vq.bytes[6], vq.bytes[7]);
+    }
+    __syncthreads();
+    // V codes: one 32-bit word = one channel x (8 | 16) tokens of one quad
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(lds_codes);
+    uint32_t *vc = reinterpret_cast<uint32_t *>(rec + R::kVCodes);
+    constexpr int n_words = R::kCodeBytes / 4;
+#pragma unroll
+    for (int widx = tid; widx < n_words; widx += 256) {
+        const int jl = widx & 3, n = (widx >> 2) & 15, quad = (widx >> 6) & 3, jh = (widx >> 8) & 1;
+        const int blk = widx >> 9;   // INT4 only (0 for INT2)
+        const int c = (jh * 4 + jl) * 16 + n;
+        uint32_t val = 0, mask = 0;
+#pragma unroll
+        for (int p = 0; p < 32 / BITS; ++p) {
+            int t;
+            if (BITS == 4) {
+                const int j = 2 * (p & 3) + (p >> 2);
+                t = 32 * blk + 16 * (j >> 2) + 4 * quad + (j & 3);
+            } else {
+                const int j = 2 * (p & 3) + (p >> 3);
+                t = 32 * ((p & 7) >> 2) + 16 * (j >> 2) + 4 * quad + (j & 3);
+            }
+            const uint32_t field = ((1u << BITS) - 1u) << (BITS * p);
+            if (lds_valid[t]) {
+                val |= (uint32_t)codes[t * kHeadDim + c] << (BITS * p);
+                mask |= field;
+            }
+        }
+        if (mask == 0xffffffffu) vc[widx] = val;
+        else if (mask) vc[widx] = (vc[widx] & ~mask) | val;
+    }
+}
+
+__global__ __launch_bounds__(256) void tkv_append_kernel(
+    uint8_t *__restrict__ pool, uint8_t *__restrict__ bit_map, const uint16_t *__restrict__ K,
+    const uint16_t *__restrict__ V, const uint8_t *__restrict__ tag_bits, int n_tokens,
+    const int32_t *__restrict__ work_pages, const int32_t *__restrict__ work_src, int n_kv_heads,
+    int n_pages_int2, int n_pages_int4, int32_t *status)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t lds_codes[kPageTokens][32];
+    __shared__ uint8_t lds_valid[kPageTokens];
+    const int w = blockIdx.x / n_kv_heads, head = blockIdx.x % n_kv_heads;
+    const int page = work_pages[w];
+    if (page < 0 || page >= n_pages_int2 + n_pages_int4) {
+        if (status && threadIdx.x == 0) atomicOr(status, TKV_STATUS_PAGE_RANGE);
+        return;
+    }
+    const int bits = page < n_pages_int2 ? 2 : 4;
+    const int slot = threadIdx.x >> 2;
+    const int src = work_src[(size_t)w * kPageTokens + slot];
+    bool valid = src >= 0 && src < n_tokens;
+    if (valid && tag_bits[src] != bits) {
+        valid = false;
+        if (status && (threadIdx.x & 3) == 0) atomicOr(status, TKV_STATUS_TAG_MISMATCH);
+    }
+    uint8_t *rec = pool + record_offset(page, head, n_kv_heads, n_pages_int2);
+    if (bits == 2) append_record<2>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid);
+    else append_record<4>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid);
+    if (head == 0 && __syncthreads_or(valid) && threadIdx.x == 0) bit_map[page] = (uint8_t)bits;
+}
+
+} // namespace
+
+int tkv_launch_append(const tkv_desc *desc, void *pool, uint8_t *bit_map, const void *K, const void *V,
+                      const uint8_t *tag_bits, int32_t n_tokens, const int32_t *work_pages,
+                      const int32_t *work_src, int32_t n_work, int32_t *status, void *stream)
+{
+    const dim3 grid((unsigned)(n_work * desc->n_kv_heads)), block(256);
+    hipLaunchKernelGGL(tkv_append_kernel, grid, block, 0, (hipStream_t)stream, (uint8_t *)pool, bit_map,
+                       (const uint16_t *)K, (const uint16_t *)V, tag_bits, n_tokens, work_pages, work_src,
+                       desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4, status);
+    return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
+}

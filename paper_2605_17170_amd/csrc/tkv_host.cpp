@@ -1,0 +1,393 @@
+// Host side of libtkv: geometry, the two page allocators, per-sequence page
+// tables, the append and decode planners, and argument validation in front of
+// the kernel launchers.  Nothing here touches the GPU; the launchers live in
+// tkv_append.hip and tkv_decode.hip.
+//
+// Paper passages: offset-split shared address space and one allocator per
+// pool, Sec. 3.2.2; per-token bitwidth array routing tokens to the pools and
+// the INT2-first partition of the page table, Sec. 3.2.3.
+#include "tkv.h"
+#include "tkv_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr int kHeadDim = 128, kGroup = 32, kPageTokens = 64;
+
+bool desc_ok(const tkv_desc *d)
+{
+    return d && d->n_kv_heads > 0 && d->head_dim == kHeadDim && d->group_size == kGroup &&
+           d->page_tokens == kPageTokens && d->n_pages_int2 >= 0 && d->n_pages_int4 >= 0 &&
+           (int64_t)d->n_pages_int2 + d->n_pages_int4 <= INT32_MAX / kPageTokens;
+}
+
+int desc_status(const tkv_desc *d)
+{
+    if (!d) return TKV_ERR_INVALID_ARG;
+    return desc_ok(d) ? TKV_OK : TKV_ERR_BAD_SHAPE;
+}
+
+// splitmix64: seeds and drives the free-list shuffle
+inline uint64_t mix64(uint64_t &s)
+{
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+} // namespace
+
+struct tkv_alloc {
+    tkv_desc desc;
+    std::vector<int32_t> free_list[2];   // [0] INT2 pool, [1] INT4 pool; back() is handed out next
+    std::vector<uint8_t> in_use;         // per page
+};
+
+struct tkv_seq {
+    std::vector<int32_t> pages[2];
+    int32_t n_tok[2] = {0, 0};
+};
+
+extern "C" {
+
+const char *tkv_strerror(int status)
+{
+    switch (status) {
+    case TKV_OK: return "ok";
+    case TKV_ERR_INVALID_ARG: return "invalid argument";
+    case TKV_ERR_BAD_BITS: return "bitwidth is not 2 or 4";
+    case TKV_ERR_BAD_SHAPE: return "unsupported shape";
+    case TKV_ERR_PAGE_RANGE: return "page id out of range";
+    case TKV_ERR_POOL_EXHAUSTED: return "pool exhausted";
+    case TKV_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case TKV_ERR_HIP: return "HIP launch failed";
+    case TKV_ERR_CAPACITY: return "output array too small";
+    default: return "unknown status";
+    }
+}
+
+size_t tkv_record_bytes(int bits)
+{
+    if (bits != 2 && bits != 4) return 0;
+    const size_t codes = (size_t)kPageTokens * kHeadDim * bits / 8;
+    const size_t meta = (size_t)kPageTokens * (kHeadDim / kGroup) * 2;   // fp16 per (token, group)
+    return 2 * (codes + 2 * meta);
+}
+
+size_t tkv_page_bytes(const tkv_desc *desc, int bits)
+{
+    if (!desc_ok(desc)) return 0;
+    return tkv_record_bytes(bits) * (size_t)desc->n_kv_heads;
+}
+
+size_t tkv_pool_bytes(const tkv_desc *desc)
+{
+    if (!desc_ok(desc)) return 0;
+    return tkv_page_bytes(desc, 2) * (size_t)desc->n_pages_int2 +
+           tkv_page_bytes(desc, 4) * (size_t)desc->n_pages_int4;
+}
+
+size_t tkv_record_offset(const tkv_desc *desc, int32_t page, int32_t head)
+{
+    if (!desc_ok(desc) || page < 0 || head < 0 || head >= desc->n_kv_heads ||
+        page >= desc->n_pages_int2 + desc->n_pages_int4)
+        return (size_t)-1;
+    if (page < desc->n_pages_int2)
+        return ((size_t)page * desc->n_kv_heads + head) * tkv_record_bytes(2);
+    return tkv_page_bytes(desc, 2) * (size_t)desc->n_pages_int2 +
+           ((size_t)(page - desc->n_pages_int2) * desc->n_kv_heads + head) * tkv_record_bytes(4);
+}
+
+/* ---------------------------------------------------------------- allocator */
+
+int tkv_alloc_create(const tkv_desc *desc, uint64_t shuffle_seed, tkv_alloc **out)
+{
+    if (!out) return TKV_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (int st = desc_status(desc)) return st;
+    tkv_alloc *a = new (std::nothrow) tkv_alloc;
+    if (!a) return TKV_ERR_INVALID_ARG;
+    a->desc = *desc;
+    const int32_t n[2] = {desc->n_pages_int2, desc->n_pages_int4};
+    const int32_t base[2] = {0, desc->n_pages_int2};
+    a->in_use.assign((size_t)n[0] + n[1], 0);
+    uint64_t state = shuffle_seed;
+    for (int p = 0; p < 2; ++p) {
+        auto &fl = a->free_list[p];
+        fl.resize((size_t)n[p]);
+        // back() is handed out first: store in decreasing order so that
+        // an unshuffled allocator returns increasing page ids
+        for (int32_t i = 0; i < n[p]; ++i) fl[(size_t)i] = base[p] + n[p] - 1 - i;
+        if (shuffle_seed)
+            for (int32_t i = n[p] - 1; i > 0; --i)
+                std::swap(fl[(size_t)i], fl[(size_t)(mix64(state) % (uint64_t)(i + 1))]);
+    }
+    *out = a;
+    return TKV_OK;
+}
+
+void tkv_alloc_destroy(tkv_alloc *a) { delete a; }
+
+int tkv_alloc_pages(tkv_alloc *a, int bits, int32_t n, int32_t *page_ids_out)
+{
+    if (!a || n < 0 || (n > 0 && !page_ids_out)) return TKV_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return TKV_ERR_BAD_BITS;
+    auto &fl = a->free_list[bits == 4];
+    if ((size_t)n > fl.size()) return TKV_ERR_POOL_EXHAUSTED;
+    for (int32_t i = 0; i < n; ++i) {
+        page_ids_out[i] = fl.back();
+        fl.pop_back();
+        a->in_use[(size_t)page_ids_out[i]] = 1;
+    }
+    return TKV_OK;
+}
+
+int tkv_free_pages(tkv_alloc *a, const int32_t *page_ids, int32_t n)
+{
+    if (!a || n < 0 || (n > 0 && !page_ids)) return TKV_ERR_INVALID_ARG;
+    const int32_t total = a->desc.n_pages_int2 + a->desc.n_pages_int4;
+    // validate first (including duplicates inside the request), then free
+    std::vector<int32_t> sorted(page_ids, page_ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t p = sorted[(size_t)i];
+        if (p < 0 || p >= total || !a->in_use[(size_t)p]) return TKV_ERR_PAGE_RANGE;
+        if (i && sorted[(size_t)i - 1] == p) return TKV_ERR_PAGE_RANGE;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t p = page_ids[i];
+        a->in_use[(size_t)p] = 0;
+        a->free_list[p >= a->desc.n_pages_int2].push_back(p);
+    }
+    return TKV_OK;
+}
+
+int32_t tkv_alloc_free_count(const tkv_alloc *a, int bits)
+{
+    if (!a) return TKV_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return TKV_ERR_BAD_BITS;
+    return (int32_t)a->free_list[bits == 4].size();
+}
+
+/* ---------------------------------------------------------------- sequences */
+
+int tkv_seq_create(tkv_seq **out)
+{
+    if (!out) return TKV_ERR_INVALID_ARG;
+    *out = new (std::nothrow) tkv_seq;
+    return *out ? TKV_OK : TKV_ERR_INVALID_ARG;
+}
+
+void tkv_seq_destroy(tkv_seq *s) { delete s; }
+
+int tkv_seq_release(tkv_seq *s, tkv_alloc *a)
+{
+    if (!s || !a) return TKV_ERR_INVALID_ARG;
+    for (int p = 0; p < 2; ++p) {
+        int st = tkv_free_pages(a, s->pages[p].data(), (int32_t)s->pages[p].size());
+        if (st) return st;
+        s->pages[p].clear();
+        s->n_tok[p] = 0;
+    }
+    return TKV_OK;
+}
+
+int32_t tkv_seq_n_tokens(const tkv_seq *s, int bits)
+{
+    if (!s) return TKV_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return TKV_ERR_BAD_BITS;
+    return s->n_tok[bits == 4];
+}
+
+int32_t tkv_seq_n_pages(const tkv_seq *s, int bits)
+{
+    if (!s) return TKV_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return TKV_ERR_BAD_BITS;
+    return (int32_t)s->pages[bits == 4].size();
+}
+
+int32_t tkv_seq_page_ids(const tkv_seq *s, int32_t *out, int32_t capacity)
+{
+    if (!s || capacity < 0 || (capacity > 0 && !out)) return TKV_ERR_INVALID_ARG;
+    const size_t n = s->pages[0].size() + s->pages[1].size();
+    if (n > (size_t)capacity) return TKV_ERR_CAPACITY;
+    if (!s->pages[0].empty()) std::memcpy(out, s->pages[0].data(), s->pages[0].size() * sizeof(int32_t));
+    if (!s->pages[1].empty())
+        std::memcpy(out + s->pages[0].size(), s->pages[1].data(), s->pages[1].size() * sizeof(int32_t));
+    return (int32_t)n;
+}
+
+/* ---------------------------------------------------------------- Q1: append plan */
+
+int32_t tkv_plan_append_max_work(int32_t n_tokens)
+{
+    if (n_tokens < 0) return TKV_ERR_INVALID_ARG;
+    // each width touches at most one partly filled page plus ceil(n/64) new ones
+    return n_tokens / kPageTokens + 4;
+}
+
+int tkv_plan_append(tkv_alloc *a, tkv_seq *s, const uint8_t *tag_bits, int32_t n_tokens,
+                    int32_t token_base, int32_t *slot_ids_out, int32_t *work_pages_out,
+                    int32_t *work_src_out, int32_t max_work, int32_t *n_work_out)
+{
+    if (!a || !s || n_tokens < 0 || token_base < 0 || max_work < 0 || !n_work_out) return TKV_ERR_INVALID_ARG;
+    if (n_tokens > 0 && (!tag_bits || !slot_ids_out)) return TKV_ERR_INVALID_ARG;
+    if (max_work > 0 && (!work_pages_out || !work_src_out)) return TKV_ERR_INVALID_ARG;
+    if ((int64_t)token_base + n_tokens > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    *n_work_out = 0;
+    int32_t n_new[2] = {0, 0};
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        if (tag_bits[t] != 2 && tag_bits[t] != 4) return TKV_ERR_BAD_BITS;
+        ++n_new[tag_bits[t] == 4];
+    }
+    int32_t room[2], new_pages[2], touched = 0;
+    for (int p = 0; p < 2; ++p) {
+        room[p] = (int32_t)s->pages[p].size() * kPageTokens - s->n_tok[p];   // free slots of the open page
+        new_pages[p] = n_new[p] > room[p] ? ceil_div(n_new[p] - room[p], kPageTokens) : 0;
+        if ((size_t)new_pages[p] > a->free_list[p].size()) return TKV_ERR_POOL_EXHAUSTED;
+        touched += new_pages[p] + (n_new[p] > 0 && room[p] > 0);
+    }
+    if (touched > max_work) return TKV_ERR_CAPACITY;
+
+    // commit: take pages, then lay the work list out as [INT2 pages..., INT4 pages...]
+    int32_t first_work[2], first_page_index[2];
+    int32_t w = 0;
+    for (int p = 0; p < 2; ++p) {
+        const bool open = n_new[p] > 0 && room[p] > 0;
+        first_page_index[p] = (int32_t)s->pages[p].size() - (open ? 1 : 0);   // index in the stream of the first touched page
+        const size_t old = s->pages[p].size();
+        s->pages[p].resize(old + (size_t)new_pages[p]);
+        tkv_alloc_pages(a, p ? 4 : 2, new_pages[p], s->pages[p].data() + old);   // cannot fail: checked above
+        first_work[p] = w;
+        if (n_new[p] == 0) continue;
+        for (size_t i = (size_t)first_page_index[p]; i < s->pages[p].size(); ++i) work_pages_out[w++] = s->pages[p][i];
+    }
+    std::fill(work_src_out, work_src_out + (size_t)w * kPageTokens, -1);
+    int32_t cursor[2] = {s->n_tok[0], s->n_tok[1]};   // position in the stream of the next token
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        const int p = tag_bits[t] == 4;
+        const int32_t pos = cursor[p]++;
+        const int32_t page_index = pos / kPageTokens, slot = pos % kPageTokens;
+        slot_ids_out[t] = s->pages[p][(size_t)page_index] * kPageTokens + slot;
+        work_src_out[(size_t)(first_work[p] + page_index - first_page_index[p]) * kPageTokens + slot] = token_base + t;
+    }
+    s->n_tok[0] = cursor[0];
+    s->n_tok[1] = cursor[1];
+    *n_work_out = w;
+    return TKV_OK;
+}
+
+/* ---------------------------------------------------------------- D1: decode plan */
+
+int32_t tkv_plan_decode_capacity(int32_t batch, int32_t target_items)
+{
+    if (batch < 0 || target_items < 1 || (int64_t)batch + target_items > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    return batch + target_items;
+}
+
+int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page_indptr,
+                        const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                        int32_t target_items, int32_t *items_out, int32_t capacity,
+                        int32_t *seq_item_indptr_out)
+{
+    if (int st = desc_status(desc)) return st;
+    if (batch < 0 || target_items < 1 || capacity < 0 || !page_indptr || !seq_item_indptr_out) return TKV_ERR_INVALID_ARG;
+    if (batch > 0 && (!n_tok_int2 || !n_tok_int4)) return TKV_ERR_INVALID_ARG;
+    if (capacity > 0 && !items_out) return TKV_ERR_INVALID_ARG;
+    constexpr int64_t kCost2 = 3, kCost4 = 5;   // bytes of an INT2 : INT4 record = 6144 : 10240
+    int64_t total = 0;
+    for (int32_t b = 0; b < batch; ++b) {
+        if (n_tok_int2[b] < 0 || n_tok_int4[b] < 0) return TKV_ERR_INVALID_ARG;
+        const int32_t p2 = ceil_div(n_tok_int2[b], kPageTokens), p4 = ceil_div(n_tok_int4[b], kPageTokens);
+        if (page_indptr[b + 1] - page_indptr[b] != p2 + p4) return TKV_ERR_INVALID_ARG;
+        total += kCost2 * p2 + kCost4 * p4;
+    }
+    const int64_t per_item = std::max<int64_t>(1, (total + target_items - 1) / target_items);
+    int32_t n_items = 0;
+    seq_item_indptr_out[0] = 0;
+    for (int32_t b = 0; b < batch; ++b) {
+        const int32_t p2 = ceil_div(n_tok_int2[b], kPageTokens), p4 = ceil_div(n_tok_int4[b], kPageTokens);
+        const int32_t pages = p2 + p4;
+        const int64_t cost = kCost2 * p2 + kCost4 * p4;
+        if (pages > 0) {
+            const int32_t n_split = (int32_t)std::min<int64_t>(pages, std::max<int64_t>(1, (cost + per_item / 2) / per_item));
+            if (n_items + n_split > capacity) return TKV_ERR_CAPACITY;
+            int32_t begin = 0;
+            int64_t cum = 0;   // cost of pages [0, begin)
+            for (int32_t k = 0; k < n_split; ++k) {
+                const int64_t goal = cost * (k + 1) / n_split;
+                int32_t end = begin;
+                while (end < pages && (end == begin || cum + (end < p2 ? kCost2 : kCost4) <= goal)) {
+                    cum += end < p2 ? kCost2 : kCost4;
+                    ++end;
+                }
+                end = std::min(end, pages - (n_split - 1 - k));   // leave a page for every later item
+                if (k == n_split - 1) end = pages;
+                // recompute cum if the clamp moved `end` backwards
+                cum = kCost2 * std::min(end, p2) + kCost4 * std::max(0, end - p2);
+                int32_t *it = items_out + 4 * (size_t)n_items++;
+                it[0] = b; it[1] = begin; it[2] = end; it[3] = 0;
+                begin = end;
+            }
+        }
+        seq_item_indptr_out[b + 1] = n_items;
+    }
+    return n_items;
+}
+
+/* ---------------------------------------------------------------- device entry points */
+
+int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
+                        const void *K, const void *V, const uint8_t *tag_bits,
+                        int32_t n_tokens, int32_t group_size,
+                        const int32_t *work_pages, const int32_t *work_src, int32_t n_work,
+                        int32_t *status, void *stream)
+{
+    if (int st = desc_status(desc)) return st;
+    if (group_size != kGroup) return TKV_ERR_BAD_SHAPE;
+    if (n_tokens < 0 || n_work < 0) return TKV_ERR_INVALID_ARG;
+    if (n_work == 0) return TKV_OK;
+    if (!pool || !bit_map || !K || !V || !tag_bits || !work_pages || !work_src) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15)) return TKV_ERR_INVALID_ARG;
+    if ((int64_t)n_work * desc->n_kv_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_append(desc, pool, bit_map, K, V, tag_bits, n_tokens, work_pages, work_src, n_work, status, stream);
+}
+
+size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t n_q_heads)
+{
+    if (!desc_ok(desc) || n_items < 0 || n_q_heads <= 0) return 0;
+    return (size_t)n_items * (size_t)n_q_heads * (size_t)(desc->head_dim + 2) * sizeof(float);
+}
+
+int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                         const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                         const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                         const int32_t *items, const int32_t *seq_item_indptr, int32_t n_items,
+                         int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
+                         void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
+{
+    if (int st = desc_status(desc)) return st;
+    if (batch < 0 || n_items < 0 || n_q_heads <= 0) return TKV_ERR_INVALID_ARG;
+    if (n_q_heads % desc->n_kv_heads) return TKV_ERR_BAD_SHAPE;
+    const int r = n_q_heads / desc->n_kv_heads;
+    if (r != 1 && r != 2 && r != 4 && r != 8) return TKV_ERR_BAD_SHAPE;
+    if (batch == 0) return TKV_OK;
+    if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
+    if (!q || !out || !page_indptr || !n_tok_int2 || !n_tok_int4 || !seq_item_indptr) return TKV_ERR_INVALID_ARG;
+    if (n_items > 0 && (!pool || !bit_map || !page_ids || !items || !workspace)) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)q & 15) || ((uintptr_t)out & 15) || ((uintptr_t)workspace & 15))
+        return TKV_ERR_INVALID_ARG;
+    if (workspace_bytes < tkv_decode_workspace_bytes(desc, n_items, n_q_heads)) return TKV_ERR_WORKSPACE_TOO_SMALL;
+    if ((int64_t)n_items * desc->n_kv_heads > INT32_MAX || (int64_t)batch * n_q_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_decode(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                             seq_item_indptr, n_items, batch, n_q_heads, sm_scale, out, workspace, status, stream);
+}
+
+} // extern "C"

@@ -1,0 +1,46 @@
+// Device-side constants of the page layout (fixed geometry: 64 tokens per
+// page, head_dim 128, groups of 32 channels).  A record holds one (page, kv
+// head): K codes | K scale | K zero | V codes | V scale | V zero.  The INT2
+// pool precedes the INT4 pool in one address space split by an offset
+// (paper Sec. 3.2.2).
+#ifndef TKV_LAYOUT_H
+#define TKV_LAYOUT_H
+
+#include <stdint.h>
+
+namespace tkv {
+
+constexpr int kPageTokens = 64;
+constexpr int kHeadDim = 128;
+constexpr int kGroup = 32;
+constexpr int kGroups = kHeadDim / kGroup;       // 4
+constexpr int kMetaBytes = kPageTokens * kGroups * 2;   // one fp16 plane: 512 B
+
+template <int BITS> struct Rec {
+    static constexpr int kCodeBytes = kPageTokens * kHeadDim * BITS / 8;   // 2048 / 4096
+    static constexpr int kKCodes = 0;
+    static constexpr int kKScale = kCodeBytes;
+    static constexpr int kKZero = kCodeBytes + kMetaBytes;
+    static constexpr int kVCodes = kCodeBytes + 2 * kMetaBytes;
+    static constexpr int kVScale = 2 * kCodeBytes + 2 * kMetaBytes;
+    static constexpr int kVZero = 2 * kCodeBytes + 3 * kMetaBytes;
+    static constexpr int kBytes = 2 * kCodeBytes + 4 * kMetaBytes;         // 6144 / 10240
+};
+
+// Byte offset of the record of (page, head); the caller has checked the range.
+__host__ __device__ inline int64_t record_offset(int page, int head, int n_kv_heads, int n_pages_int2)
+{
+    if (page < n_pages_int2) return ((int64_t)page * n_kv_heads + head) * Rec<2>::kBytes;
+    return (int64_t)n_pages_int2 * n_kv_heads * Rec<2>::kBytes +
+           ((int64_t)(page - n_pages_int2) * n_kv_heads + head) * Rec<4>::kBytes;
+}
+
+// fp16 index of (token t, group g) in the V scale / V zero planes: chunks of 8
+// tokens [t/32][(t%16)/4][g][j], j = 4*((t/16)%2) + t%4.
+__host__ __device__ inline int vmeta_index(int t, int g)
+{
+    return ((((t >> 5) * 4 + ((t & 15) >> 2)) * 4 + g) << 3) + (((t >> 4) & 1) << 2) + (t & 3);
+}
+
+} // namespace tkv
+#endif

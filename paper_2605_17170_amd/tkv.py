@@ -1,0 +1,298 @@
+"""ctypes binding of libtkv (include/tkv.h): same names, argument marshalling
+only.  Device buffers are torch tensors (torch is used for device memory and
+streams, nothing else); host arrays are numpy.  Every step of the path runs in
+the library's HIP kernels -- there is no fallback: if the library has not been
+built, importing a function here raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtkv.so")
+
+TKV_OK = 0
+TKV_ERR_INVALID_ARG = -1
+TKV_ERR_BAD_BITS = -2
+TKV_ERR_BAD_SHAPE = -3
+TKV_ERR_PAGE_RANGE = -4
+TKV_ERR_POOL_EXHAUSTED = -5
+TKV_ERR_WORKSPACE_TOO_SMALL = -6
+TKV_ERR_HIP = -7
+TKV_ERR_CAPACITY = -8
+TKV_STATUS_TAG_MISMATCH = 1
+TKV_STATUS_BITMAP_MISMATCH = 2
+TKV_STATUS_PAGE_RANGE = 4
+
+PAGE_TOKENS = 64
+HEAD_DIM = 128
+GROUP_SIZE = 32
+
+EXPORTS = [
+    "tkv_strerror", "tkv_record_bytes", "tkv_page_bytes", "tkv_pool_bytes", "tkv_record_offset",
+    "tkv_alloc_create", "tkv_alloc_destroy", "tkv_alloc_pages", "tkv_free_pages", "tkv_alloc_free_count",
+    "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
+    "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append",
+    "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
+]
+
+
+class TkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, strerror(status), status))
+
+
+class tkv_desc(C.Structure):
+    _fields_ = [("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("group_size", C.c_int32),
+                ("page_tokens", C.c_int32), ("n_pages_int2", C.c_int32), ("n_pages_int4", C.c_int32)]
+
+    @classmethod
+    def make(cls, n_kv_heads, n_pages_int2, n_pages_int4, head_dim=HEAD_DIM, group_size=GROUP_SIZE,
+             page_tokens=PAGE_TOKENS):
+        return cls(n_kv_heads, head_dim, group_size, page_tokens, n_pages_int2, n_pages_int4)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libtkv.so is not built: run `python -m paper_2605_17170_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        dp = C.POINTER(tkv_desc)
+        L.tkv_strerror.restype = C.c_char_p
+        L.tkv_strerror.argtypes = [C.c_int]
+        L.tkv_record_bytes.restype = sz
+        L.tkv_record_bytes.argtypes = [C.c_int]
+        L.tkv_page_bytes.restype = sz
+        L.tkv_page_bytes.argtypes = [dp, C.c_int]
+        L.tkv_pool_bytes.restype = sz
+        L.tkv_pool_bytes.argtypes = [dp]
+        L.tkv_record_offset.restype = sz
+        L.tkv_record_offset.argtypes = [dp, i32, i32]
+        L.tkv_alloc_create.argtypes = [dp, C.c_uint64, C.POINTER(vp)]
+        L.tkv_alloc_destroy.restype = None
+        L.tkv_alloc_destroy.argtypes = [vp]
+        L.tkv_alloc_pages.argtypes = [vp, C.c_int, i32, vp]
+        L.tkv_free_pages.argtypes = [vp, vp, i32]
+        L.tkv_alloc_free_count.restype = i32
+        L.tkv_alloc_free_count.argtypes = [vp, C.c_int]
+        L.tkv_seq_create.argtypes = [C.POINTER(vp)]
+        L.tkv_seq_destroy.restype = None
+        L.tkv_seq_destroy.argtypes = [vp]
+        L.tkv_seq_release.argtypes = [vp, vp]
+        L.tkv_seq_n_tokens.restype = i32
+        L.tkv_seq_n_tokens.argtypes = [vp, C.c_int]
+        L.tkv_seq_n_pages.restype = i32
+        L.tkv_seq_n_pages.argtypes = [vp, C.c_int]
+        L.tkv_seq_page_ids.restype = i32
+        L.tkv_seq_page_ids.argtypes = [vp, vp, i32]
+        L.tkv_plan_append_max_work.restype = i32
+        L.tkv_plan_append_max_work.argtypes = [i32]
+        L.tkv_plan_append.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, C.POINTER(i32)]
+        L.tkv_quantize_append.argtypes = [dp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
+        L.tkv_plan_decode_capacity.restype = i32
+        L.tkv_plan_decode_capacity.argtypes = [i32, i32]
+        L.tkv_plan_decode.restype = i32
+        L.tkv_plan_decode.argtypes = [dp, i32, vp, vp, vp, i32, vp, i32, vp]
+        L.tkv_decode_workspace_bytes.restype = sz
+        L.tkv_decode_workspace_bytes.argtypes = [dp, i32, i32]
+        L.tkv_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float,
+                                           vp, vp, sz, vp, vp]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().tkv_strerror(status).decode()
+
+
+def _check(status: int, where: str):
+    if status < 0:
+        raise TkvError(status, where)
+    return status
+
+
+def _np(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, C.c_void_p(a.ctypes.data if a.size else None)
+
+
+def _dev(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(None)
+    assert t.is_contiguous(), "device arguments must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+# ---------------------------------------------------------------- geometry
+def tkv_record_bytes(bits: int) -> int:
+    return int(lib().tkv_record_bytes(bits))
+
+
+def tkv_page_bytes(desc: tkv_desc, bits: int) -> int:
+    return int(lib().tkv_page_bytes(C.byref(desc), bits))
+
+
+def tkv_pool_bytes(desc: tkv_desc) -> int:
+    return int(lib().tkv_pool_bytes(C.byref(desc)))
+
+
+def tkv_record_offset(desc: tkv_desc, page: int, head: int) -> int:
+    v = int(lib().tkv_record_offset(C.byref(desc), page, head))
+    return -1 if v == C.c_size_t(-1).value else v
+
+
+# ---------------------------------------------------------------- allocator / sequences (host)
+def tkv_alloc_create(desc: tkv_desc, shuffle_seed: int = 0):
+    h = C.c_void_p()
+    _check(lib().tkv_alloc_create(C.byref(desc), shuffle_seed, C.byref(h)), "tkv_alloc_create")
+    return h
+
+
+def tkv_alloc_destroy(a):
+    lib().tkv_alloc_destroy(a)
+
+
+def tkv_alloc_pages(a, bits: int, n: int) -> np.ndarray:
+    out = np.empty(max(n, 0), np.int32)
+    _check(lib().tkv_alloc_pages(a, bits, n, C.c_void_p(out.ctypes.data if n > 0 else None)), "tkv_alloc_pages")
+    return out
+
+
+def tkv_free_pages(a, page_ids):
+    ids, p = _np(page_ids, np.int32)
+    _check(lib().tkv_free_pages(a, p, ids.size), "tkv_free_pages")
+
+
+def tkv_alloc_free_count(a, bits: int) -> int:
+    return _check(lib().tkv_alloc_free_count(a, bits), "tkv_alloc_free_count")
+
+
+def tkv_seq_create():
+    h = C.c_void_p()
+    _check(lib().tkv_seq_create(C.byref(h)), "tkv_seq_create")
+    return h
+
+
+def tkv_seq_destroy(s):
+    lib().tkv_seq_destroy(s)
+
+
+def tkv_seq_release(s, a):
+    _check(lib().tkv_seq_release(s, a), "tkv_seq_release")
+
+
+def tkv_seq_n_tokens(s, bits: int) -> int:
+    return _check(lib().tkv_seq_n_tokens(s, bits), "tkv_seq_n_tokens")
+
+
+def tkv_seq_n_pages(s, bits: int) -> int:
+    return _check(lib().tkv_seq_n_pages(s, bits), "tkv_seq_n_pages")
+
+
+def tkv_seq_page_ids(s) -> np.ndarray:
+    n = tkv_seq_n_pages(s, 2) + tkv_seq_n_pages(s, 4)
+    out = np.empty(n, np.int32)
+    got = _check(lib().tkv_seq_page_ids(s, C.c_void_p(out.ctypes.data if n else None), n), "tkv_seq_page_ids")
+    assert got == n
+    return out
+
+
+# ---------------------------------------------------------------- Q1 (host)
+def tkv_plan_append_max_work(n_tokens: int) -> int:
+    return _check(lib().tkv_plan_append_max_work(n_tokens), "tkv_plan_append_max_work")
+
+
+def tkv_plan_append(a, s, tag_bits, token_base: int = 0):
+    """Returns (slot_ids i32[n], work_pages i32[n_work], work_src i32[n_work, 64])."""
+    bits, pb = _np(tag_bits, np.uint8)
+    n = bits.size
+    cap = tkv_plan_append_max_work(n)
+    slots = np.empty(n, np.int32)
+    wp = np.empty(cap, np.int32)
+    ws = np.empty((cap, PAGE_TOKENS), np.int32)
+    nw = C.c_int32(0)
+    _check(lib().tkv_plan_append(a, s, pb, n, token_base, C.c_void_p(slots.ctypes.data if n else None),
+                                 C.c_void_p(wp.ctypes.data), C.c_void_p(ws.ctypes.data), cap, C.byref(nw)),
+           "tkv_plan_append")
+    return slots, wp[:nw.value].copy(), ws[:nw.value].copy()
+
+
+# ---------------------------------------------------------------- Q2-Q5 (device)
+def tkv_quantize_append(desc, pool, bit_map, K, V, tag_bits, work_pages, work_src, status=None, stream=None,
+                        group_size: int = GROUP_SIZE):
+    """All array arguments are torch device tensors: pool u8, bit_map u8,
+    K/V bf16 [T,Hkv,D], tag_bits u8[T], work_pages i32[n_work], work_src i32[n_work,64]."""
+    n_tokens = int(K.shape[0]) if K is not None else 0
+    n_work = int(work_pages.numel()) if work_pages is not None else 0
+    if K is not None:
+        assert tuple(V.shape) == tuple(K.shape) == (n_tokens, desc.n_kv_heads, desc.head_dim)
+        assert K.element_size() == 2 and V.element_size() == 2 and tag_bits.numel() == n_tokens
+    if n_work:
+        assert work_src.numel() == n_work * desc.page_tokens and work_src.element_size() == 4
+        assert pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
+        assert bit_map.numel() >= desc.n_pages_int2 + desc.n_pages_int4
+    _check(lib().tkv_quantize_append(C.byref(desc), _dev(pool), _dev(bit_map), _dev(K), _dev(V), _dev(tag_bits),
+                                     n_tokens, group_size, _dev(work_pages), _dev(work_src), n_work,
+                                     _dev(status), _stream(stream)), "tkv_quantize_append")
+
+
+# ---------------------------------------------------------------- D1 (host)
+def tkv_plan_decode_capacity(batch: int, target_items: int) -> int:
+    return _check(lib().tkv_plan_decode_capacity(batch, target_items), "tkv_plan_decode_capacity")
+
+
+def tkv_plan_decode(desc, page_indptr, n_tok_int2, n_tok_int4, target_items: int):
+    """Returns (items i32[n_items, 4], seq_item_indptr i32[batch+1])."""
+    ip, pip = _np(page_indptr, np.int32)
+    n2, p2 = _np(n_tok_int2, np.int32)
+    n4, p4 = _np(n_tok_int4, np.int32)
+    batch = ip.size - 1
+    cap = tkv_plan_decode_capacity(batch, target_items)
+    items = np.empty((cap, 4), np.int32)
+    sip = np.empty(batch + 1, np.int32)
+    n = _check(lib().tkv_plan_decode(C.byref(desc), batch, pip, p2, p4, target_items,
+                                     C.c_void_p(items.ctypes.data), cap, C.c_void_p(sip.ctypes.data)),
+               "tkv_plan_decode")
+    return items[:n].copy(), sip
+
+
+# ---------------------------------------------------------------- D2-D7 (device)
+def tkv_decode_workspace_bytes(desc, n_items: int, n_q_heads: int) -> int:
+    return int(lib().tkv_decode_workspace_bytes(C.byref(desc), n_items, n_q_heads))
+
+
+def tkv_decode_attention(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                         seq_item_indptr, sm_scale: float, out, workspace, status=None, stream=None):
+    """Device tensors: q bf16 [B,Hq,D]; page_indptr i32[B+1]; page_ids i32; n_tok_int2/4 i32[B];
+    items i32[n_items,4]; seq_item_indptr i32[B+1]; out f32 [B,Hq,D]; workspace u8."""
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    n_items = int(items.shape[0]) if items is not None else 0
+    ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    assert q.element_size() == 2 and int(q.shape[2]) == desc.head_dim
+    assert page_indptr.numel() == batch + 1 and seq_item_indptr.numel() == batch + 1
+    assert n_tok_int2.numel() == batch and n_tok_int4.numel() == batch
+    assert out.numel() == batch * n_q_heads * desc.head_dim and out.element_size() == 4
+    if n_items:
+        assert items.numel() == 4 * n_items and pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
+    _check(lib().tkv_decode_attention(C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr),
+                                      _dev(page_ids), _dev(n_tok_int2), _dev(n_tok_int4), _dev(items),
+                                      _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
+                                      _dev(out), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
+           "tkv_decode_attention")
