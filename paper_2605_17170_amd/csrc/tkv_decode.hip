@@ -42,6 +42,13 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
+#ifndef TKV_PREFETCH
+#define TKV_PREFETCH 1
+#endif
+#ifndef TKV_WAVES_PER_EU
+#define TKV_WAVES_PER_EU 2
+#endif
+
 constexpr float kTau = 4.0f;       // rescale when a logit exceeds the reference maximum by this much (log2 units)
 constexpr float kOBase = 1.0f;     // common power-of-two factor on P: P = p * 2^(kOBase + o_slot)
 
@@ -355,15 +362,24 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
     int page;
     bool ok;
     fetch(pb, page, ok);
-    PageRegs<BITS> cur, nxt;
+    PageRegs<BITS> cur;
+#if TKV_PREFETCH
+    PageRegs<BITS> nxt;
     load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
     nxt = cur;
+#endif
     for (int pi = pb; pi < pe; ++pi) {
+#if TKV_PREFETCH
         const bool cur_ok = ok;
         if (pi + 1 < pe) {
             fetch(pi + 1, page, ok);
             load_page<BITS>(nxt, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
         }
+#else
+        if (pi > pb) fetch(pi, page, ok);
+        const bool cur_ok = ok;
+        load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
+#endif
         int nv = pi == last_index ? last_valid : kPageTokens;
         if (cur.bm != BITS && cur_ok) {
             if (status && lane == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
@@ -372,11 +388,13 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
         if (!cur_ok) nv = 0;
         if (nv == kPageTokens) compute_page<BITS, false>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
         else compute_page<BITS, true>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
+#if TKV_PREFETCH
         cur = nxt;
+#endif
     }
 }
 
-__global__ __launch_bounds__(64) void tkv_decode_kernel(
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PER_EU, TKV_WAVES_PER_EU))) void tkv_decode_kernel(
     const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map, const uint16_t *__restrict__ q,
     const int32_t *__restrict__ page_indptr, const int32_t *__restrict__ page_ids,
     const int32_t *__restrict__ n_tok_int2, const int32_t *__restrict__ n_tok_int4,
@@ -490,24 +508,55 @@ __global__ __launch_bounds__(64) void tkv_decode_kernel(
     }
 }
 
-// D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence
-__global__ __launch_bounds__(kHeadDim) void tkv_reduce_kernel(
+// D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence.
+// One workgroup per (sequence, query head): the items' maxima are reduced in parallel, the weights go
+// to LDS, then four groups of 128 threads (one thread per channel) each sum every fourth item.
+constexpr int kReduceParts = 4;
+__global__ __launch_bounds__(kHeadDim * kReduceParts) void tkv_reduce_kernel(
     const float *__restrict__ acc_ws, const float *__restrict__ ml_ws, const int32_t *__restrict__ seq_item_indptr,
     int n_q_heads, float *__restrict__ out)
 {
-    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, c = threadIdx.x;
+    constexpr int kThreads = kHeadDim * kReduceParts, kChunk = 512;
+    __shared__ float w_s[kChunk];
+    __shared__ float red[kThreads / 64];
+    __shared__ float part_s[kReduceParts][kHeadDim];
+    __shared__ float den_s[kReduceParts];
+    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, tid = threadIdx.x;
+    const int c = tid % kHeadDim, part = tid / kHeadDim;
     const int i0 = seq_item_indptr[b], i1 = seq_item_indptr[b + 1];
+    // global maximum of the items' reference maxima
     float M = -INFINITY;
-    for (int i = i0; i < i1; ++i) M = fmaxf(M, ml_ws[2 * ((size_t)i * n_q_heads + h)]);
+    for (int i = i0 + tid; i < i1; i += kThreads) M = fmaxf(M, ml_ws[2 * ((size_t)i * n_q_heads + h)]);
+    M = wave_max(M);
+    if ((tid & 63) == 0) red[tid >> 6] = M;
+    __syncthreads();
+    M = red[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / 64; ++k) M = fmaxf(M, red[k]);
     float num = 0.0f, den = 0.0f;
-    if (M != -INFINITY)
-        for (int i = i0; i < i1; ++i) {
-            const size_t ph = (size_t)i * n_q_heads + h;
-            const float w = __builtin_amdgcn_exp2f(ml_ws[2 * ph] - M);
-            num = fmaf(w, acc_ws[ph * kHeadDim + c], num);
-            den = fmaf(w, ml_ws[2 * ph + 1], den);
+    if (M != -INFINITY) {
+        for (int base = i0; base < i1; base += kChunk) {
+            const int n = i1 - base < kChunk ? i1 - base : kChunk;
+            __syncthreads();
+            if (tid < n) w_s[tid] = __builtin_amdgcn_exp2f(ml_ws[2 * ((size_t)(base + tid) * n_q_heads + h)] - M);
+            __syncthreads();
+#pragma unroll 4
+            for (int k = part; k < n; k += kReduceParts) {
+                const size_t ph = (size_t)(base + k) * n_q_heads + h;
+                num = fmaf(w_s[k], acc_ws[ph * kHeadDim + c], num);
+                if (c == 0) den = fmaf(w_s[k], ml_ws[2 * ph + 1], den);
+            }
         }
-    out[((size_t)b * n_q_heads + h) * kHeadDim + c] = den > 0.0f ? num / den : 0.0f;
+    }
+    part_s[part][c] = num;
+    if (c == 0) den_s[part] = den;
+    __syncthreads();
+    if (part == 0) {
+        float nsum = 0.0f, dsum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kReduceParts; ++k) { nsum += part_s[k][c]; dsum += den_s[k]; }
+        out[((size_t)b * n_q_heads + h) * kHeadDim + c] = dsum > 0.0f ? nsum / dsum : 0.0f;
+    }
 }
 
 } // namespace
@@ -528,7 +577,7 @@ int tkv_launch_decode(const tkv_desc *desc, const void *pool, const uint8_t *bit
                            desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status);
         if (hipGetLastError() != hipSuccess) return TKV_ERR_HIP;
     }
-    hipLaunchKernelGGL(tkv_reduce_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kHeadDim), 0,
+    hipLaunchKernelGGL(tkv_reduce_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kHeadDim * kReduceParts), 0,
                        (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
 }
