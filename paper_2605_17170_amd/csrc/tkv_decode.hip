@@ -3,15 +3,9 @@
 // (paper Sec. 3.2.3 "Decode": KV processed as parallel contiguous splits,
 // each running one dequantisation path, merged by online log-sum-exp).
 //
-// One workgroup of four wavefronts owns one (work item, kv head): a contiguous
-// range of one sequence's page list, walked page by page.  All query heads
-// that share the kv head (up to 8) are processed together so the packed KV
-// bytes are read from HBM once.  Inside a page the four wavefronts split the
-// work: wavefront w computes QK^T and the softmax numerators of tokens
-// 16w..16w+15, publishes them through LDS (one barrier per page), and
-// accumulates PV for channels 32w..32w+31 over all 64 tokens.  The small
-// per-wavefront state (about a hundred VGPRs) lets many wavefronts share a
-// SIMD, which is what hides MFMA, LDS and HBM latency here.
+// One wavefront owns one (work item, kv head): a contiguous range of one
+// sequence's page list.  All query heads that share the kv head (up to 8)
+// are processed together so the packed KV bytes are read from HBM once.
 //
 // Matrix cores do both contractions (v_mfma_f32_16x16x32_f16), fp32 accumulate:
 //
@@ -48,8 +42,11 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
+#ifndef TKV_PREFETCH
+#define TKV_PREFETCH 1
+#endif
 #ifndef TKV_WAVES_PER_EU
-#define TKV_WAVES_PER_EU 4
+#define TKV_WAVES_PER_EU 2
 #endif
 
 constexpr float kTau = 4.0f;       // rescale when a logit exceeds the reference maximum by this much (log2 units)
@@ -111,25 +108,19 @@ template <int BITS> __device__ __forceinline__ constexpr int o_slot(int j)
     return BITS == 4 ? ((j & 2) ? 6 : 10) : 10 - 2 * (j >> 1);
 }
 
-constexpr int kWaves = 4;   // wavefronts per workgroup; wavefront w: token tile w, channel tiles 2w, 2w+1 (group w)
 struct WaveState {
-    floatx4 acc[2];     // PV accumulators: channel tile 2w + t2, rows 4*q4 + i (rows 0..7 hi piece of P, 8..15 lo piece)
-    floatx4 zacc;       // column 0: zero-term of group w; column 1: softmax denominator
-    floatx4 m_row;      // reference maximum of rows 4*q4 + i (log2 units)
-    float m_col;        // reference maximum of this lane's head column
+    floatx4 acc[8];     // PV accumulators: tile jt (16 channels) x rows (4*q4 + i)
+    floatx4 zacc;       // zero-term (cols 0..3 = groups) and denominator (col 4)
+    float m_ref;        // reference maximum of this lane's head column, log2 units, -inf before the first page
 };
 
-constexpr int kStageBufs = 3;
 struct alignas(16) Lds {
-    alignas(16) float ks[kStageBufs][kPageTokens * kGroups];             // K scale * F, fp32 [token][group]
-    alignas(16) uint32_t vs_hi[kStageBufs][kPageTokens * kGroups / 2];   // V scale, 7-bit piece, fp16 pairs in plane order
-    alignas(16) uint32_t vs_lo[kStageBufs][kPageTokens * kGroups / 2];   // V scale, remainder
-    alignas(16) uint32_t vz[kStageBufs][kPageTokens * kGroups / 2];      // V zero * 2^-o_slot
-    alignas(16) uint2 pbuf[2][4][64];                                    // P pieces [parity][tile][lane]
-    alignas(16) float mx[2][kWaves][16];                                 // tile maxima [parity][wave][head column]
-    int over[2][kWaves];                                                 // [parity][wave]: a maximum outgrew the reference
-    alignas(16) float qf[8][kHeadDim];
-    alignas(16) float zl[kWaves][8][2];
+    alignas(16) float ks[kPageTokens * kGroups];          // K scale * F, fp32 [token][group]
+    alignas(16) uint32_t vs_hi[kPageTokens * kGroups / 2];  // V scale, 7-bit piece, fp16 pairs in plane order
+    alignas(16) uint32_t vs_lo[kPageTokens * kGroups / 2];  // V scale, remainder
+    alignas(16) uint32_t vz[kPageTokens * kGroups / 2];     // V zero * 2^-o_slot
+    alignas(16) float alpha[16];
+    alignas(16) float zl[16][8];
 };
 
 // B operand of the QK^T MFMAs for one width: per group, 4 registers of fp16
@@ -162,119 +153,94 @@ __device__ __forceinline__ void build_q_operand(const float *qf /* this lane's h
         }
 }
 
-// What one wavefront loads for one (page, kv head) record: the codes it consumes itself ...
-template <int BITS> struct CodeRegs {
-    uint4 kw;                  // K codes of tile w: four groups of this lane's channel slice
-    uint2 kz;                  // K zero of token 16*w + lane%16, four groups
-    uint2 vw[BITS / 2];        // V codes of channel tiles 2w, 2w+1 (INT4: one pair per 32-token block)
-};
-// ... and its share of the metadata planes that the workgroup stages in LDS (threads 0..127: entries
-// 2t, 2t+1 of the K scale / V scale / V zero planes), fetched two pages ahead.
-struct MetaRegs {
-    uint32_t ksc, vsc, vzc;
-    uint32_t bm;               // bit_map entry of the page
-    int nv;                    // valid tokens of the page (0 if its id was flagged)
+// Everything one wavefront loads for one (page, kv head) record.
+template <int BITS> struct PageRegs {
+    uint4 kw[4];          // K codes: one 16-byte chunk per 16-token tile (four groups of this lane's channel slice)
+    uint4 vw[BITS];       // V codes: 16-byte chunks, one word per 16-channel tile
+    uint2 ksc, vsc, vzc;  // this lane's four entries of the K scale / V scale / V zero planes
+    uint2 kz[4];          // K zero of token 16*e + lane%16, four groups
+    uint32_t bm;          // bit_map entry of the page
 };
 
 template <int BITS>
-__device__ __forceinline__ void load_codes(CodeRegs<BITS> &cr, const uint8_t *__restrict__ rec, int w, int lane)
+__device__ __forceinline__ void load_page(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec,
+                                          const uint8_t *__restrict__ bit_map, int page, int lane)
 {
     using R = Rec<BITS>;
     const int r16 = lane & 15, q4 = lane >> 4;
     const uint4 *kc = reinterpret_cast<const uint4 *>(rec + R::kKCodes);
-    cr.kw = BITS == 4 ? kc[w * 64 + lane] : kc[w * 32 + (q4 >> 1) * 16 + r16];
-    cr.kz = reinterpret_cast<const uint2 *>(rec + R::kKZero)[16 * w + r16];
-    // a 16-byte chunk of V codes holds the words of four channel tiles; this wavefront needs two of them
-    const uint2 *vc2 = reinterpret_cast<const uint2 *>(rec + R::kVCodes) + (w & 1);
-    if (BITS == 4) {
+    const uint4 *vc = reinterpret_cast<const uint4 *>(rec + R::kVCodes);
 #pragma unroll
-        for (int blk = 0; blk < BITS / 2; ++blk) cr.vw[blk] = vc2[2 * ((blk * 2 + (w >> 1)) * 64 + lane)];
-    } else {
-        cr.vw[0] = vc2[2 * ((w >> 1) * 64 + lane)];
-    }
+    for (int e = 0; e < 4; ++e)
+        pr.kw[e] = BITS == 4 ? kc[e * 64 + lane] : kc[e * 32 + (q4 >> 1) * 16 + r16];
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) pr.vw[i] = vc[i * 64 + lane];
+    pr.ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[lane];
+    pr.vsc = reinterpret_cast<const uint2 *>(rec + R::kVScale)[lane];
+    pr.vzc = reinterpret_cast<const uint2 *>(rec + R::kVZero)[lane];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pr.kz[e] = reinterpret_cast<const uint2 *>(rec + R::kKZero)[16 * e + r16];
+    pr.bm = bit_map[page];
 }
 
-template <int BITS>
-__device__ __forceinline__ void load_meta(MetaRegs &mr, const uint8_t *__restrict__ rec,
-                                          const uint8_t *__restrict__ bit_map, int page, int tid)
-{
-    using R = Rec<BITS>;
-    if (tid < 128) {
-        mr.ksc = reinterpret_cast<const uint32_t *>(rec + R::kKScale)[tid];
-        mr.vsc = reinterpret_cast<const uint32_t *>(rec + R::kVScale)[tid];
-        mr.vzc = reinterpret_cast<const uint32_t *>(rec + R::kVZero)[tid];
-    }
-    mr.bm = bit_map[page];
-}
-
-// Convert this thread's share of the three metadata planes and put it in stage buffer `sb`:
-// K scale -> fp32 times F; V scale -> 7-bit piece + remainder; V zero times 2^-o_slot.  Entries of tokens
-// at or beyond n_valid are zeroed in the V planes (their P is zero, the product must not be NaN).
-template <int BITS>
-__device__ __forceinline__ void stage_meta(const MetaRegs &pr, int n_valid, int tid, float F, Lds &lds, int sb)
-{
-    if (tid >= 128) return;
-    const half2_t ks = __builtin_bit_cast(half2_t, pr.ksc);
-    reinterpret_cast<float2 *>(lds.ks[sb])[tid] = make_float2((float)ks[0] * F, (float)ks[1] * F);
-    uint32_t vsc = pr.vsc, vzc = pr.vzc;
-    // entries 2t, 2t+1: chunk t/4 = (block, quad, group), slots j = 2*(t%4), +1
-    const int chunk = tid >> 2, blk = chunk >> 4, quad = (chunk >> 2) & 3, j = 2 * (tid & 3);
-    if (n_valid < kPageTokens) {
-        const int t0 = 32 * blk + 16 * (j >> 2) + 4 * quad + (j & 3);
-        const uint32_t m = (t0 < n_valid ? 0xffffu : 0u) | (t0 + 1 < n_valid ? 0xffff0000u : 0u);
-        vsc &= m;
-        vzc &= m;
-    }
-    const uint32_t hi = vsc & 0xfff0fff0u;
-    const half2_t lo = __builtin_bit_cast(half2_t, vsc) - __builtin_bit_cast(half2_t, hi);
-    lds.vs_hi[sb][tid] = hi;
-    lds.vs_lo[sb][tid] = __builtin_bit_cast(uint32_t, lo);
-    const int o = o_slot<BITS>(j);   // same for both slots of the pair
-    const _Float16 f = o == 10 ? (_Float16)0x1p-10f : o == 8 ? (_Float16)0x1p-8f : o == 6 ? (_Float16)0x1p-6f : (_Float16)0x1p-4f;
-    const half2_t z = __builtin_bit_cast(half2_t, vzc) * f;
-    lds.vz[sb][tid] = __builtin_bit_cast(uint32_t, z);
-}
-
-// One page: `cur` holds its codes; its metadata is already staged in buffer sb and published by a
-// barrier.  The metadata of the next page (`nxt`, loaded an iteration earlier) is staged into buffer
-// sb_next before this page's barrier.
-// Number of valid tokens of a page whose metadata has arrived: a bit_map entry that does not match
-// the page's position in the list masks the whole page.
-template <int BITS> __device__ __forceinline__ int checked_valid(const MetaRegs &mr, int tid, int32_t *status)
-{
-    if (mr.bm != BITS && mr.nv > 0) {
-        if (status && tid == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
-        return 0;
-    }
-    return mr.nv;
-}
-
-template <int BITS>
-__device__ __forceinline__ int page_step(const CodeRegs<BITS> &cur, int n_valid, bool have_next,
-                                         const MetaRegs &nxt, int sb, int sb_next, int par,
-                                         int w, int lane, int tid, const QOperand &qo, half8 qz, float F,
-                                         float kappa, float negk, WaveState &st, Lds &lds, int32_t *status)
+template <int BITS, bool PARTIAL>
+__device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_valid, int lane,
+                                             const QOperand &qo, half8 qz, float F, float kappa,
+                                             float negk, WaveState &st, Lds &lds)
 {
     const int r16 = lane & 15, q4 = lane >> 4;
-    const bool partial = n_valid < kPageTokens;
 
-    // ---- QK^T for tile w: S[i] = q . k_hat (unscaled), token 16w + 4*q4 + i, head column r16
-    floatx4 S;
+    // ---- stage metadata in LDS --------------------------------------------
+    __syncthreads();   // previous page's readers are done
     {
-        const half8 za = as_half8(cur.kz.x, cur.kz.y, cur.kz.x, cur.kz.y);
+        uint2 vsc = pr.vsc, vzc = pr.vzc;
+        const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
+        reinterpret_cast<float4 *>(lds.ks)[lane] =
+            make_float4((float)a[0] * F, (float)a[1] * F, (float)b[0] * F, (float)b[1] * F);
+        // this lane holds plane entries 4*lane .. 4*lane+3: chunk lane/2, slots 4*(lane&1) + 0..3
+        if (PARTIAL) {
+            const int chunk = lane >> 1, blk = chunk >> 4, quad = (chunk >> 2) & 3, jb = 4 * (lane & 1);
+            const int t0 = 32 * blk + 16 * (jb >> 2) + 4 * quad;   // tokens t0 .. t0+3
+            const uint32_t m01 = (t0 < n_valid ? 0xffffu : 0u) | (t0 + 1 < n_valid ? 0xffff0000u : 0u);
+            const uint32_t m23 = (t0 + 2 < n_valid ? 0xffffu : 0u) | (t0 + 3 < n_valid ? 0xffff0000u : 0u);
+            vsc.x &= m01; vsc.y &= m23; vzc.x &= m01; vzc.y &= m23;
+        }
+        const uint32_t hx = vsc.x & 0xfff0fff0u, hy = vsc.y & 0xfff0fff0u;
+        const half2_t lx = __builtin_bit_cast(half2_t, vsc.x) - __builtin_bit_cast(half2_t, hx);
+        const half2_t ly = __builtin_bit_cast(half2_t, vsc.y) - __builtin_bit_cast(half2_t, hy);
+        reinterpret_cast<uint2 *>(lds.vs_hi)[lane] = make_uint2(hx, hy);
+        reinterpret_cast<uint2 *>(lds.vs_lo)[lane] =
+            make_uint2(__builtin_bit_cast(uint32_t, lx), __builtin_bit_cast(uint32_t, ly));
+        // zero plane times 2^-o_slot: slots 4*(lane&1)+{0,1} and +{2,3}
+        const int j0 = 4 * (lane & 1);
+        float f01, f23;
+        if (BITS == 4) { f01 = 0x1p-10f; f23 = 0x1p-6f; }
+        else { f01 = j0 ? 0x1p-6f : 0x1p-10f; f23 = j0 ? 0x1p-4f : 0x1p-8f; }
+        const half2_t z01 = __builtin_bit_cast(half2_t, vzc.x) * (_Float16)f01;
+        const half2_t z23 = __builtin_bit_cast(half2_t, vzc.y) * (_Float16)f23;
+        reinterpret_cast<uint2 *>(lds.vz)[lane] =
+            make_uint2(__builtin_bit_cast(uint32_t, z01), __builtin_bit_cast(uint32_t, z23));
+    }
+    __syncthreads();
+
+    // ---- QK^T: S[e][i] = q . k_hat (unscaled) for token 16e + 4*q4 + i, head column r16
+    floatx4 S[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const half8 za = as_half8(pr.kz[e].x, pr.kz[e].y, pr.kz[e].x, pr.kz[e].y);
         floatx4 s = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});
         float4 sc[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sc[i] = reinterpret_cast<const float4 *>(lds.ks[sb])[16 * w + 4 * q4 + i];
-        const uint32_t wd[4] = {cur.kw.x, cur.kw.y, cur.kw.z, cur.kw.w};
+        for (int i = 0; i < 4; ++i) sc[i] = reinterpret_cast<const float4 *>(lds.ks)[16 * e + 4 * q4 + i];
+        const uint32_t w[4] = {pr.kw[e].x, pr.kw[e].y, pr.kw[e].z, pr.kw[e].w};
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             half8 a;
             if (BITS == 4) {
-                const uint32_t w8 = wd[g] >> 8;
-                a = as_half8(wd[g] & 0x000f000fu, wd[g] & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u);
+                const uint32_t w8 = w[g] >> 8;
+                a = as_half8(w[g] & 0x000f000fu, w[g] & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u);
             } else {
-                const uint32_t ws = wd[g] >> (8 * (q4 & 1));
+                const uint32_t ws = w[g] >> (8 * (q4 & 1));
                 a = as_half8(ws & 0x00030003u, ws & 0x000c000cu, ws & 0x00300030u, ws & 0x00c000c0u);
             }
             const half8 b = as_half8(qo.r[g][0], qo.r[g][1], qo.r[g][2], qo.r[g][3]);
@@ -285,163 +251,150 @@ __device__ __forceinline__ int page_step(const CodeRegs<BITS> &cur, int n_valid,
                 s[i] = fmaf(scg, p[i], s[i]);
             }
         }
-        if (partial)
+        if (PARTIAL)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (16 * w + 4 * q4 + i >= n_valid) s[i] = -INFINITY;
-        S = s;
+                if (16 * e + 4 * q4 + i >= n_valid) s[i] = -INFINITY;
+        S[e] = s;
     }
 
-    // ---- softmax numerators against the current reference maximum (tentative) ----
-    float mx = fmaxf(fmaxf(S[0], S[1]), fmaxf(S[2], S[3]));
+    // ---- online softmax with a lazily updated reference maximum ------------
+    float mx = fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3]));
+#pragma unroll
+    for (int e = 1; e < 4; ++e) mx = fmaxf(fmaxf(mx, S[e][0]), fmaxf(fmaxf(S[e][1], S[e][2]), S[e][3]));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     mx *= kappa;   // log2 units
-    const int over = __any(mx > st.m_col + kTau);
-    auto numerators = [&](float m_col) {
-        const float mref = m_col == -INFINITY ? 0.0f : m_col;
+    if (__any(mx > st.m_ref + kTau)) {
+        const float m_new = fmaxf(st.m_ref, mx);
+        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m_ref - m_new);
+        st.m_ref = m_new;
+        __syncthreads();
+        if (q4 == 0) lds.alpha[r16] = alpha;
+        __syncthreads();
+        const float4 al = reinterpret_cast<const float4 *>(lds.alpha)[q4];   // rows 4*q4 .. 4*q4+3
+        const floatx4 av = {al.x, al.y, al.z, al.w};
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt) st.acc[jt] *= av;
+        st.zacc *= av;
+    }
+    const float mref = st.m_ref == -INFINITY ? 0.0f : st.m_ref;
+    uint32_t pa[2][4];   // A operand of the two PV contraction blocks
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
         float pv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            // tile w is tile (w & 1) of block w / 2: slot j = 4 * (w & 1) + i; o_slot does not depend on bit 2 of j
-            const float off = (kOBase + (float)o_slot<BITS>(i)) - mref;
-            const float off2 = (kOBase + (float)o_slot<BITS>(4 + i)) - mref;
-            pv[i] = __builtin_amdgcn_exp2f(fmaf(S[i], kappa, (w & 1) ? off2 : off));
+            const int j = 4 * (e & 1) + i;
+            const float off = (kOBase + (float)o_slot<BITS>(j)) - mref;
+            pv[i] = __builtin_amdgcn_exp2f(fmaf(S[e][i], kappa, off));
         }
-        lds.pbuf[par][w][lane] = make_uint2(p_piece(pv[0], pv[1], negk), p_piece(pv[2], pv[3], negk));
-    };
-    numerators(st.m_col);
-    if (q4 == 0) lds.mx[par][w][r16] = mx;
-    if (lane == 0) lds.over[par][w] = over;
-    int n_valid_next = 0;
-    if (have_next) {
-        n_valid_next = checked_valid<BITS>(nxt, tid, status);
-        stage_meta<BITS>(nxt, n_valid_next, tid, F, lds, sb_next);
-    }
-    __syncthreads();
-
-    if (lds.over[par][0] | lds.over[par][1] | lds.over[par][2] | lds.over[par][3]) {
-        // a logit outgrew the reference: every wavefront raises it, rescales and redoes its numerators
-        float m_new = st.m_col;
-        floatx4 mr = st.m_row;
-#pragma unroll
-        for (int k = 0; k < kWaves; ++k) {
-            m_new = fmaxf(m_new, lds.mx[par][k][r16]);
-            const float4 a = reinterpret_cast<const float4 *>(lds.mx[par][k])[q4];
-            mr = floatx4{fmaxf(mr[0], a.x), fmaxf(mr[1], a.y), fmaxf(mr[2], a.z), fmaxf(mr[3], a.w)};
-        }
-        floatx4 al;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) al[i] = mr[i] == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m_row[i] - mr[i]);
-        st.m_row = mr;
-        st.acc[0] *= al;
-        st.acc[1] *= al;
-        st.zacc *= al;
-        st.m_col = m_new;
-        numerators(m_new);
-        __syncthreads();
+        pa[e >> 1][2 * (e & 1)] = p_piece(pv[0], pv[1], negk);
+        pa[e >> 1][2 * (e & 1) + 1] = p_piece(pv[2], pv[3], negk);
     }
 
-    // ---- PV for channel tiles 2w, 2w+1 (group w) over all 64 tokens ----------------
+    // ---- PV ------------------------------------------------------------------
     constexpr uint32_t kOne = 0x3c003c00u;
     uint32_t one = kOne;
     asm volatile("" : "+v"(one));   // keep the constant in a VGPR (operand of v_and_or_b32)
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
-        const uint2 pa0 = lds.pbuf[par][2 * blk][lane], pa1 = lds.pbuf[par][2 * blk + 1][lane];
-        const half8 p8 = as_half8(pa0.x, pa0.y, pa1.x, pa1.y);
-        // zero term and denominator: column 0 = group w; other columns = constants 2^-o_slot
+        const half8 p8 = as_half8(pa[blk][0], pa[blk][1], pa[blk][2], pa[blk][3]);
+        // zero term and denominator: columns 0..3 = groups, column 4 = constants 2^-o_slot
         {
-            uint4 bz = reinterpret_cast<const uint4 *>(lds.vz[sb])[(blk * 4 + q4) * 4 + w];
-            if (r16 >= 1) {
+            uint4 bz = reinterpret_cast<const uint4 *>(lds.vz)[(blk * 4 + q4) * 4 + (r16 & 3)];
+            if (r16 >= 4) {
                 if (BITS == 4) bz = make_uint4(0x14001400u, 0x24002400u, 0x14001400u, 0x24002400u);   // 2^-10, 2^-6
                 else bz = make_uint4(0x14001400u, 0x1c001c00u, 0x24002400u, 0x2c002c00u);           // 2^-10 .. 2^-4
             }
             st.zacc = mfma(p8, as_half8(bz.x, bz.y, bz.z, bz.w), st.zacc);
         }
-        const uint4 shi = reinterpret_cast<const uint4 *>(lds.vs_hi[sb])[(blk * 4 + q4) * 4 + w];
-        const uint4 slo = reinterpret_cast<const uint4 *>(lds.vs_lo[sb])[(blk * 4 + q4) * 4 + w];
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-            const uint2 v = BITS == 4 ? cur.vw[blk] : cur.vw[0];
-            const uint32_t wd = t2 == 0 ? v.x : v.y;
-            uint32_t x[4];
-            if (BITS == 4) {
-                const uint32_t w8 = wd >> 8;
-                x[0] = and_or(wd, 0x000f000fu, one); x[1] = and_or(wd, 0x00f000f0u, one);
-                x[2] = and_or(w8, 0x000f000fu, one); x[3] = and_or(w8, 0x00f000f0u, one);
-            } else {
-                const uint32_t ws = blk ? (wd >> 8) : wd;
-                x[0] = and_or(ws, 0x00030003u, one); x[1] = and_or(ws, 0x000c000cu, one);
-                x[2] = and_or(ws, 0x00300030u, one); x[3] = and_or(ws, 0x00c000c0u, one);
+        for (int g = 0; g < 4; ++g) {
+            const uint4 shi = reinterpret_cast<const uint4 *>(lds.vs_hi)[(blk * 4 + q4) * 4 + g];
+            const uint4 slo = reinterpret_cast<const uint4 *>(lds.vs_lo)[(blk * 4 + q4) * 4 + g];
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                const int jt = 2 * g + t2;
+                uint32_t w;
+                {
+                    const uint4 v = BITS == 4 ? pr.vw[blk * 2 + (jt >> 2)] : pr.vw[jt >> 2];
+                    w = (jt & 3) == 0 ? v.x : (jt & 3) == 1 ? v.y : (jt & 3) == 2 ? v.z : v.w;
+                }
+                uint32_t x[4];
+                if (BITS == 4) {
+                    const uint32_t w8 = w >> 8;
+                    x[0] = and_or(w, 0x000f000fu, one); x[1] = and_or(w, 0x00f000f0u, one);
+                    x[2] = and_or(w8, 0x000f000fu, one); x[3] = and_or(w8, 0x00f000f0u, one);
+                } else {
+                    const uint32_t ws = blk ? (w >> 8) : w;
+                    x[0] = and_or(ws, 0x00030003u, one); x[1] = and_or(ws, 0x000c000cu, one);
+                    x[2] = and_or(ws, 0x00300030u, one); x[3] = and_or(ws, 0x00c000c0u, one);
+                }
+                const half8 bh = as_half8(pk_fma(x[0], shi.x), pk_fma(x[1], shi.y), pk_fma(x[2], shi.z), pk_fma(x[3], shi.w));
+                const half8 bl = as_half8(pk_fma(x[0], slo.x), pk_fma(x[1], slo.y), pk_fma(x[2], slo.z), pk_fma(x[3], slo.w));
+                st.acc[jt] = mfma(p8, bh, st.acc[jt]);
+                st.acc[jt] = mfma(p8, bl, st.acc[jt]);
             }
-            const half8 bh = as_half8(pk_fma(x[0], shi.x), pk_fma(x[1], shi.y), pk_fma(x[2], shi.z), pk_fma(x[3], shi.w));
-            const half8 bl = as_half8(pk_fma(x[0], slo.x), pk_fma(x[1], slo.y), pk_fma(x[2], slo.z), pk_fma(x[3], slo.w));
-            st.acc[t2] = mfma(p8, bh, st.acc[t2]);
-            st.acc[t2] = mfma(p8, bl, st.acc[t2]);
         }
     }
-    return n_valid_next;
 }
 
-// All pages [pb, pe) of one width (indices into the sequence's page list), the wavefronts in lockstep.
+// All pages [pb, pe) of one width (indices into the sequence's page list).  Loads of the next page
+// are issued before the current page is computed.
 template <int BITS>
 __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map,
                                           const int32_t *__restrict__ pages, int pb, int pe, int last_index,
                                           int last_valid, int page_lo, int page_hi, int n_pages_total, int kvh,
-                                          int n_kv_heads, int n_pages_int2, int w, int lane, int tid,
-                                          const QOperand &qo, half8 qz, float F, float kappa, float negk,
-                                          WaveState &st, Lds &lds, int32_t *status)
+                                          int n_kv_heads, int n_pages_int2, int lane, const QOperand &qo, half8 qz,
+                                          float F, float kappa, float negk, WaveState &st, Lds &lds, int32_t *status)
 {
-    // Page id of list position pi, with its number of valid tokens (0 for a page that is flagged: an id
-    // outside its pool cannot be addressed, so a valid page is read instead and fully masked).
-    auto locate = [&](int pi, int &nv) -> const uint8_t * {
-        int page = pages[pi];
-        const bool ok = page >= page_lo && page < page_hi;
+    // a page id outside its pool cannot be addressed: it is flagged, replaced by a valid page and masked out
+    auto fetch = [&](int pi, int &page, bool &ok) {
+        page = pages[pi];
+        ok = page >= page_lo && page < page_hi;
         if (!ok) {
-            if (status && tid == 0)
+            if (status && lane == 0)
                 atomicOr(status, page < 0 || page >= n_pages_total ? TKV_STATUS_PAGE_RANGE : TKV_STATUS_BITMAP_MISMATCH);
             page = page_lo;
         }
-        nv = ok ? (pi == last_index ? last_valid : kPageTokens) : 0;
-        return pool + record_offset(page, kvh, n_kv_heads, n_pages_int2);
     };
-    auto fetch_codes = [&](int pi, CodeRegs<BITS> &cr) {
-        int nv;
-        load_codes<BITS>(cr, locate(pi, nv), w, lane);
-    };
-    auto fetch_meta = [&](int pi, MetaRegs &mr) {
-        int page = pages[pi];
-        page = page >= page_lo && page < page_hi ? page : page_lo;
-        load_meta<BITS>(mr, locate(pi, mr.nv), bit_map, page, tid);
-    };
-    CodeRegs<BITS> C0, C1;
-    MetaRegs M0, M1;
-    fetch_meta(pb, M0);
-    fetch_codes(pb, C0);
-    if (pb + 1 < pe) fetch_meta(pb + 1, M1);
-    int nv0 = checked_valid<BITS>(M0, tid, status), nv1 = 0;
-    __syncthreads();   // every reader of the stage buffers of an earlier stream is done
-    stage_meta<BITS>(M0, nv0, tid, F, lds, 0);
-    __syncthreads();
-    int sb = 0;
-    for (int pi = pb; pi < pe; pi += 2) {
-        const int sb1 = sb == 2 ? 0 : sb + 1, sb2 = sb1 == 2 ? 0 : sb1 + 1;
-        const bool n1 = pi + 1 < pe, n2 = pi + 2 < pe, n3 = pi + 3 < pe;
-        // codes one page ahead; metadata two pages ahead (it is staged one page before it is used)
-        if (n1) fetch_codes(pi + 1, C1);
-        if (n2) fetch_meta(pi + 2, M0);   // M0 held page pi, which is staged already
-        nv1 = page_step<BITS>(C0, nv0, n1, M1, sb, sb1, 0, w, lane, tid, qo, qz, F, kappa, negk, st, lds, status);
-        if (!n1) break;
-        if (n2) fetch_codes(pi + 2, C0);
-        if (n3) fetch_meta(pi + 3, M1);   // M1 held page pi + 1, staged by the step above
-        nv0 = page_step<BITS>(C1, nv1, n2, M0, sb1, sb2, 1, w, lane, tid, qo, qz, F, kappa, negk, st, lds, status);
-        sb = sb2;
+    int page;
+    bool ok;
+    fetch(pb, page, ok);
+    PageRegs<BITS> cur;
+#if TKV_PREFETCH
+    PageRegs<BITS> nxt;
+    load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
+    nxt = cur;
+#endif
+    for (int pi = pb; pi < pe; ++pi) {
+#if TKV_PREFETCH
+        const bool cur_ok = ok;
+        if (pi + 1 < pe) {
+            fetch(pi + 1, page, ok);
+            load_page<BITS>(nxt, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
+        }
+#else
+        if (pi > pb) fetch(pi, page, ok);
+        const bool cur_ok = ok;
+        load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
+#endif
+        int nv = pi == last_index ? last_valid : kPageTokens;
+        if (cur.bm != BITS && cur_ok) {
+            if (status && lane == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
+            nv = 0;
+        }
+        if (!cur_ok) nv = 0;
+        if (nv == kPageTokens) compute_page<BITS, false>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
+        else compute_page<BITS, true>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
+#if TKV_PREFETCH
+        cur = nxt;
+#endif
     }
 }
 
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PER_EU, TKV_WAVES_PER_EU)))
-void tkv_decode_kernel(
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PER_EU, TKV_WAVES_PER_EU))) void tkv_decode_kernel(
     const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map, const uint16_t *__restrict__ q,
     const int32_t *__restrict__ page_indptr, const int32_t *__restrict__ page_ids,
     const int32_t *__restrict__ n_tok_int2, const int32_t *__restrict__ n_tok_int4,
@@ -449,8 +402,8 @@ void tkv_decode_kernel(
     float kappa, float *__restrict__ acc_ws, float *__restrict__ ml_ws, int32_t *status)
 {
     __shared__ Lds lds;
-    const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, q4 = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    __shared__ float qf[8][kHeadDim];
+    const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
     const int seq = items[4 * item];
@@ -465,16 +418,13 @@ void tkv_decode_kernel(
 
     // ---- q: load the R heads, common power-of-two normalisation, group sums ----
     float amax = 0.0f;
-    for (int idx = tid; idx < R * kHeadDim; idx += 64 * kWaves) {
+    for (int idx = lane; idx < R * kHeadDim; idx += 64) {
         const int h = idx / kHeadDim, c = idx % kHeadDim;
         const float v = __uint_as_float((uint32_t)q[((size_t)seq * n_q_heads + kvh * R + h) * kHeadDim + c] << 16);
-        lds.qf[h][c] = v;
+        qf[h][c] = v;
         amax = fmaxf(amax, fabsf(v));
     }
     amax = wave_max(amax);
-    if (lane == 0) lds.mx[0][w][0] = amax;
-    __syncthreads();
-    amax = fmaxf(fmaxf(lds.mx[0][0][0], lds.mx[0][1][0]), fmaxf(lds.mx[0][2][0], lds.mx[0][3][0]));
     // 2^E with max|q| * 2^E in [2^14, 2^15); E clamped so every factor stays a normal fp32
     int ex = 0;
     if (amax > 0.0f) { (void)frexpf(amax, &ex); }   // amax = m * 2^ex, m in [0.5, 1)
@@ -482,6 +432,7 @@ void tkv_decode_kernel(
     E = E > 100 ? 100 : (E < -100 ? -100 : E);
     const float two_e = ldexpf(1.0f, amax > 0.0f ? E : 0);
     const float F = ldexpf(1.0f, 24 - (amax > 0.0f ? E : 0));
+    __syncthreads();
     const int hcol = (r16 & 7) & (R - 1);   // head of this lane's column (columns beyond R repeat heads)
     const float negk = r16 >= 8 ? -1.0f : 0.0f;   // columns 8..15 carry the low piece of P
     half8 qz;
@@ -492,7 +443,7 @@ void tkv_decode_kernel(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             double sum = 0.0;
-            for (int c = 0; c < kGroup; ++c) sum += (double)lds.qf[hcol][g * kGroup + c];
+            for (int c = 0; c < kGroup; ++c) sum += (double)qf[hcol][g * kGroup + c];
             const _Float16 hi = (_Float16)sum;
             const double r1 = sum - (double)(float)hi;
             const _Float16 mid = (_Float16)r1;
@@ -504,40 +455,41 @@ void tkv_decode_kernel(
     }
 
     WaveState st;
-    st.acc[0] = st.acc[1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) st.acc[jt] = floatx4{0.f, 0.f, 0.f, 0.f};
     st.zacc = floatx4{0.f, 0.f, 0.f, 0.f};
-    st.m_row = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    st.m_col = -INFINITY;
+    st.m_ref = -INFINITY;
 
     const int n_pages_total = n_pages_int2 + n_pages_int4;
     QOperand qo;
     // INT2 pages of the range, then INT4 pages: each page runs one dequantisation path
     const int e2 = pe < np2 ? pe : np2;
     if (pb < e2) {
-        build_q_operand<2>(lds.qf[hcol], q4, two_e, qo);
+        build_q_operand<2>(qf[hcol], q4, two_e, qo);
         run_pages<2>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
-                     n_pages_total, kvh, n_kv_heads, n_pages_int2, w, lane, tid, qo, qz, F, kappa, negk, st, lds, status);
+                     n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qo, qz, F, kappa, negk, st, lds, status);
     }
     const int b4 = pb > np2 ? pb : np2;
     if (b4 < pe) {
-        build_q_operand<4>(lds.qf[hcol], q4, two_e, qo);
+        build_q_operand<4>(qf[hcol], q4, two_e, qo);
         run_pages<4>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
-                     n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, w, lane, tid, qo, qz, F, kappa, negk,
-                     st, lds, status);
+                     n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qo, qz, F, kappa, negk, st, lds,
+                     status);
     }
 
     // ---- write the partial (m, l, acc) of this item ------------------------------
     // rows 0..7 carry the hi piece of P, rows 8..15 the lo piece: add lanes l and l^32
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
+    for (int jt = 0; jt < 8; ++jt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st.acc[t2][i] += __shfl_xor(st.acc[t2][i], 32);
+        for (int i = 0; i < 4; ++i) st.acc[jt][i] += __shfl_xor(st.acc[jt][i], 32);
 #pragma unroll
     for (int i = 0; i < 4; ++i) st.zacc[i] += __shfl_xor(st.zacc[i], 32);
     __syncthreads();
-    if (r16 < 2 && q4 < 2)
+    if (r16 < 8 && q4 < 2)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lds.zl[w][4 * q4 + i][r16] = st.zacc[i];   // [head row][column]
+        for (int i = 0; i < 4; ++i) lds.zl[4 * q4 + i][r16] = st.zacc[i];   // [head row][column]
+    if (q4 == 0 && r16 < 8) lds.alpha[r16] = st.m_ref;
     __syncthreads();
     if (q4 < 2) {
 #pragma unroll
@@ -545,12 +497,12 @@ void tkv_decode_kernel(
             const int row = 4 * q4 + i;
             if (row >= R) continue;
             const size_t ph = (size_t)item * n_q_heads + kvh * R + row;
-            float *dst = acc_ws + ph * kHeadDim + 32 * w;
+            float *dst = acc_ws + ph * kHeadDim;
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) dst[16 * t2 + r16] = st.acc[t2][i] + lds.zl[w][row][0];
-            if (r16 == 0 && w == 0) {
-                ml_ws[2 * ph] = st.m_row[i];
-                ml_ws[2 * ph + 1] = lds.zl[0][row][1];
+            for (int jt = 0; jt < 8; ++jt) dst[16 * jt + r16] = st.acc[jt][i] + lds.zl[row][jt >> 1];
+            if (r16 == 0) {
+                ml_ws[2 * ph] = lds.alpha[row];
+                ml_ws[2 * ph + 1] = lds.zl[row][4];
             }
         }
     }
@@ -619,7 +571,7 @@ int tkv_launch_decode(const tkv_desc *desc, const void *pool, const uint8_t *bit
     float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     const float kappa = sm_scale * 1.44269504088896340736f;
     if (n_items > 0) {
-        hipLaunchKernelGGL(tkv_decode_kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64 * kWaves), 0,
+        hipLaunchKernelGGL(tkv_decode_kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64), 0,
                            (hipStream_t)stream, (const uint8_t *)pool, bit_map, (const uint16_t *)q, page_indptr,
                            page_ids, n_tok_int2, n_tok_int4, items, batch, desc->n_kv_heads, n_q_heads,
                            desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status);
