@@ -215,6 +215,23 @@ int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *
                          void *workspace, size_t workspace_bytes, int32_t *status,
                          void *stream /* hipStream_t */);
 
+/*
+ * The two launches of tkv_decode_attention as separate calls, same arguments
+ * and the same checks: D2-D6, the split kernel, which leaves one partial
+ * (m, l, acc) per work item and query head in `workspace`; and D7, the
+ * cross-split merge by log-sum-exp (Sec. 3.2.3), which reads the partials
+ * and writes `out`.  tkv_decode_attention is exactly one call of each.
+ */
+int tkv_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                     const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                     const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                     const int32_t *items, int32_t n_items, int32_t batch, int32_t n_q_heads,
+                     float sm_scale, void *workspace, size_t workspace_bytes, int32_t *status,
+                     void *stream /* hipStream_t */);
+int tkv_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int32_t n_items,
+                      int32_t batch, int32_t n_q_heads, float *out, const void *workspace,
+                      size_t workspace_bytes, void *stream /* hipStream_t */);
+
 #ifdef __cplusplus
 }
 #endif

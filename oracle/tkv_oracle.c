@@ -418,18 +418,21 @@ int tkvo_pack_pool(uint8_t *pool, uint8_t *bit_map, int Hkv, int64_t P2, int64_t
                    const uint8_t *Vc, const uint16_t *Vs, const uint16_t *Vz)
 {
     for (int64_t t = 0; t < T; ++t) {
-        int64_t page = slot_ids[t] / TP; int slot = (int)(slot_ids[t] % TP);
+        int64_t page = slot_ids[t] / TP;
         if (slot_ids[t] < 0 || page >= P2 + P4) return -1;
-        int pb = page < P2 ? 2 : 4;
-        if (bits[t] != pb) return -1;
-        bit_map[page] = (uint8_t)pb;
-        for (int h = 0; h < Hkv; ++h) {
+        if (bits[t] != (page < P2 ? 2 : 4)) return -1;
+        bit_map[page] = bits[t];
+    }
+    /* records of different kv heads never share a byte: one thread per head */
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < Hkv; ++h)
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t page = slot_ids[t] / TP; int slot = (int)(slot_ids[t] % TP);
             int64_t th = t * Hkv + h;
             uint8_t *rec = pool + tkvo_record_offset(Hkv, P2, page, h, NULL);
-            tkvo_record_put_token(rec, pb, slot, Kc + th * HD, Ks + th * NGR, Kz + th * NGR,
+            tkvo_record_put_token(rec, bits[t], slot, Kc + th * HD, Ks + th * NGR, Kz + th * NGR,
                                   Vc + th * HD, Vs + th * NGR, Vz + th * NGR);
         }
-    }
     return 0;
 }
 
@@ -439,9 +442,11 @@ int tkvo_unpack_pool(const uint8_t *pool, int Hkv, int64_t P2, int64_t P4,
                      uint8_t *Kc, uint16_t *Ks, uint16_t *Kz,
                      uint8_t *Vc, uint16_t *Vs, uint16_t *Vz)
 {
+    for (int64_t t = 0; t < T; ++t)
+        if (slot_ids[t] < 0 || slot_ids[t] / TP >= P2 + P4) return -1;
+#pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; ++t) {
         int64_t page = slot_ids[t] / TP; int slot = (int)(slot_ids[t] % TP);
-        if (slot_ids[t] < 0 || page >= P2 + P4) return -1;
         int pb;
         for (int h = 0; h < Hkv; ++h) {
             int64_t th = t * Hkv + h;

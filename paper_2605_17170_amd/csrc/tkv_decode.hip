@@ -561,22 +561,28 @@ __global__ __launch_bounds__(kHeadDim * kReduceParts) void tkv_reduce_kernel(
 
 } // namespace
 
-int tkv_launch_decode(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
-                      const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
-                      const int32_t *n_tok_int4, const int32_t *items, const int32_t *seq_item_indptr,
-                      int32_t n_items, int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
-                      void *workspace, int32_t *status, void *stream)
+int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
+                            const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
+                            const int32_t *n_tok_int4, const int32_t *items, int32_t n_items, int32_t batch,
+                            int32_t n_q_heads, float sm_scale, void *workspace, int32_t *status, void *stream)
 {
+    if (n_items == 0) return TKV_OK;
     float *acc_ws = (float *)workspace;
     float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     const float kappa = sm_scale * 1.44269504088896340736f;
-    if (n_items > 0) {
-        hipLaunchKernelGGL(tkv_decode_kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64), 0,
-                           (hipStream_t)stream, (const uint8_t *)pool, bit_map, (const uint16_t *)q, page_indptr,
-                           page_ids, n_tok_int2, n_tok_int4, items, batch, desc->n_kv_heads, n_q_heads,
-                           desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status);
-        if (hipGetLastError() != hipSuccess) return TKV_ERR_HIP;
-    }
+    hipLaunchKernelGGL(tkv_decode_kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64), 0,
+                       (hipStream_t)stream, (const uint8_t *)pool, bit_map, (const uint16_t *)q, page_indptr,
+                       page_ids, n_tok_int2, n_tok_int4, items, batch, desc->n_kv_heads, n_q_heads,
+                       desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status);
+    return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
+}
+
+int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int32_t n_items, int32_t batch,
+                             int32_t n_q_heads, float *out, const void *workspace, void *stream)
+{
+    (void)desc;
+    const float *acc_ws = (const float *)workspace;
+    const float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     hipLaunchKernelGGL(tkv_reduce_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kHeadDim * kReduceParts), 0,
                        (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;

@@ -366,6 +366,49 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
     return (size_t)n_items * (size_t)n_q_heads * (size_t)(desc->head_dim + 2) * sizeof(float);
 }
 
+namespace {
+// Checks shared by the three decode entry points.  `need_pool` / `need_out` select the arguments a call uses.
+int decode_args_status(const tkv_desc *desc, int32_t n_items, int32_t batch, int32_t n_q_heads,
+                       const void *workspace, size_t workspace_bytes)
+{
+    if (int st = desc_status(desc)) return st;
+    if (batch < 0 || n_items < 0 || n_q_heads <= 0) return TKV_ERR_INVALID_ARG;
+    if (n_q_heads % desc->n_kv_heads) return TKV_ERR_BAD_SHAPE;
+    const int r = n_q_heads / desc->n_kv_heads;
+    if (r != 1 && r != 2 && r != 4 && r != 8) return TKV_ERR_BAD_SHAPE;
+    if (n_items > 0 && !workspace) return TKV_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace & 15) return TKV_ERR_INVALID_ARG;
+    if (workspace_bytes < tkv_decode_workspace_bytes(desc, n_items, n_q_heads)) return TKV_ERR_WORKSPACE_TOO_SMALL;
+    if ((int64_t)n_items * desc->n_kv_heads > INT32_MAX || (int64_t)batch * n_q_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    return TKV_OK;
+}
+} // namespace
+
+int tkv_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                     const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                     const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                     const int32_t *items, int32_t n_items, int32_t batch, int32_t n_q_heads,
+                     float sm_scale, void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
+{
+    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
+    if (batch == 0 || n_items == 0) return TKV_OK;
+    if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
+    if (!q || !page_indptr || !n_tok_int2 || !n_tok_int4 || !pool || !bit_map || !page_ids || !items) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)q & 15)) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                                   n_items, batch, n_q_heads, sm_scale, workspace, status, stream);
+}
+
+int tkv_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int32_t n_items,
+                      int32_t batch, int32_t n_q_heads, float *out, const void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
+    if (batch == 0) return TKV_OK;
+    if (!out || !seq_item_indptr || ((uintptr_t)out & 15)) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_decode_reduce(desc, seq_item_indptr, n_items, batch, n_q_heads, out, workspace, stream);
+}
+
 int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
                          const void *q, const int32_t *page_indptr, const int32_t *page_ids,
                          const int32_t *n_tok_int2, const int32_t *n_tok_int4,
@@ -373,21 +416,17 @@ int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *
                          int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
                          void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
 {
-    if (int st = desc_status(desc)) return st;
-    if (batch < 0 || n_items < 0 || n_q_heads <= 0) return TKV_ERR_INVALID_ARG;
-    if (n_q_heads % desc->n_kv_heads) return TKV_ERR_BAD_SHAPE;
-    const int r = n_q_heads / desc->n_kv_heads;
-    if (r != 1 && r != 2 && r != 4 && r != 8) return TKV_ERR_BAD_SHAPE;
+    // validate everything both launches need before launching anything
+    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
     if (batch == 0) return TKV_OK;
     if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
     if (!q || !out || !page_indptr || !n_tok_int2 || !n_tok_int4 || !seq_item_indptr) return TKV_ERR_INVALID_ARG;
-    if (n_items > 0 && (!pool || !bit_map || !page_ids || !items || !workspace)) return TKV_ERR_INVALID_ARG;
-    if (((uintptr_t)pool & 255) || ((uintptr_t)q & 15) || ((uintptr_t)out & 15) || ((uintptr_t)workspace & 15))
-        return TKV_ERR_INVALID_ARG;
-    if (workspace_bytes < tkv_decode_workspace_bytes(desc, n_items, n_q_heads)) return TKV_ERR_WORKSPACE_TOO_SMALL;
-    if ((int64_t)n_items * desc->n_kv_heads > INT32_MAX || (int64_t)batch * n_q_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
-    return tkv_launch_decode(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
-                             seq_item_indptr, n_items, batch, n_q_heads, sm_scale, out, workspace, status, stream);
+    if (n_items > 0 && (!pool || !bit_map || !page_ids || !items)) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return TKV_ERR_INVALID_ARG;
+    if (int st = tkv_launch_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                                         n_items, batch, n_q_heads, sm_scale, workspace, status, stream))
+        return st;
+    return tkv_launch_decode_reduce(desc, seq_item_indptr, n_items, batch, n_q_heads, out, workspace, stream);
 }
 
 } // extern "C"

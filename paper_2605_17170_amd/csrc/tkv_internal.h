@@ -10,10 +10,12 @@ int tkv_launch_append(const tkv_desc *desc, void *pool, uint8_t *bit_map, const 
                       const uint8_t *tag_bits, int32_t n_tokens, const int32_t *work_pages,
                       const int32_t *work_src, int32_t n_work, int32_t *status, void *stream);
 
-int tkv_launch_decode(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
-                      const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
-                      const int32_t *n_tok_int4, const int32_t *items, const int32_t *seq_item_indptr,
-                      int32_t n_items, int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
-                      void *workspace, int32_t *status, void *stream);
+int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
+                            const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
+                            const int32_t *n_tok_int4, const int32_t *items, int32_t n_items, int32_t batch,
+                            int32_t n_q_heads, float sm_scale, void *workspace, int32_t *status, void *stream);
+
+int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int32_t n_items, int32_t batch,
+                             int32_t n_q_heads, float *out, const void *workspace, void *stream);
 
 #endif

@@ -103,6 +103,14 @@ class PagedCache:
                                  float(sm_scale), out, workspace, self.status, stream)
         return out
 
+    def decode_split(self, q: torch.Tensor, workspace, pool=None, stream=None):
+        """D2-D6 only (used by the benchmark to time the split kernel by itself)."""
+        d_items = self._plan[0]
+        sm_scale = np.float32(1.0 / math.sqrt(tkv.HEAD_DIM))
+        tkv.tkv_decode_split(self.desc, self.pool if pool is None else pool, self.bit_map, q, self.d_page_indptr,
+                             self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items, float(sm_scale), workspace,
+                             self.status, stream)
+
     def workspace(self, n_q_heads: int) -> torch.Tensor:
         n_items = self._plan[2].shape[0]
         nbytes = max(16, tkv.tkv_decode_workspace_bytes(self.desc, n_items, n_q_heads))
@@ -115,8 +123,9 @@ class PagedCache:
 
 
 def default_target_items(n_kv_heads: int, device=None) -> int:
-    """Work items over the batch: about four wavefronts per SIMD of the
-    device (one wavefront serves one item and kv head)."""
+    """Work items over the batch: one wavefront serves one (item, kv head), and
+    the decode kernel's register footprint lets two wavefronts share a SIMD,
+    so 8 per compute unit fill the device in a single round."""
     props = torch.cuda.get_device_properties(device if device is not None else torch.cuda.current_device())
-    waves = props.multi_processor_count * 4 * 4
+    waves = props.multi_processor_count * 4 * 2
     return max(1, waves // n_kv_heads)

@@ -36,6 +36,7 @@ EXPORTS = [
     "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
     "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
+    "tkv_decode_split", "tkv_decode_reduce",
 ]
 
 
@@ -106,6 +107,8 @@ def lib():
         L.tkv_decode_workspace_bytes.argtypes = [dp, i32, i32]
         L.tkv_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float,
                                            vp, vp, sz, vp, vp]
+        L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
+        L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -296,3 +299,28 @@ def tkv_decode_attention(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_in
                                       _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
                                       _dev(out), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
            "tkv_decode_attention")
+
+
+def tkv_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, sm_scale: float,
+                     workspace, status=None, stream=None):
+    """D2-D6 only: leaves the per-item partials in `workspace`."""
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    n_items = int(items.shape[0]) if items is not None else 0
+    ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    assert q.element_size() == 2 and int(q.shape[2]) == desc.head_dim and page_indptr.numel() == batch + 1
+    assert n_tok_int2.numel() == batch and n_tok_int4.numel() == batch
+    if n_items:
+        assert items.numel() == 4 * n_items and pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
+    _check(lib().tkv_decode_split(C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr), _dev(page_ids),
+                                  _dev(n_tok_int2), _dev(n_tok_int4), _dev(items), n_items, batch, n_q_heads,
+                                  float(sm_scale), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
+           "tkv_decode_split")
+
+
+def tkv_decode_reduce(desc, seq_item_indptr, n_items: int, out, workspace, stream=None):
+    """D7 only: merges the partials in `workspace` into out f32 [B,Hq,D]."""
+    batch, n_q_heads = int(out.shape[0]), int(out.shape[1])
+    ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    assert seq_item_indptr.numel() == batch + 1 and out.element_size() == 4
+    _check(lib().tkv_decode_reduce(C.byref(desc), _dev(seq_item_indptr), n_items, batch, n_q_heads, _dev(out),
+                                   _dev(workspace), ws_bytes, _stream(stream)), "tkv_decode_reduce")

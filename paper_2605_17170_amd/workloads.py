@@ -63,28 +63,36 @@ def normal_bf16(rng: np.random.Generator, shape, chunk: int = 1 << 24) -> np.nda
 
 
 def make_kv(seed_seq: np.random.SeedSequence, n_tokens: int, n_kv_heads: int,
-            outlier_channels: int = 4, outlier_scale: float = 20.0):
+            outlier_channels: int = 4, outlier_scale: float = 20.0, chunk_tokens: int = 8192):
     """K, V bf16 bits [T, Hkv, D] ~ N(0,1); per kv head, `outlier_channels`
     seeded channel indices (fixed across tokens) are scaled by `outlier_scale`
     in both K and V (key-channel outliers are the paper's stated motive for
-    its INT2 key treatment, Sec. 3.2.1).  Returns (K, V, outlier_idx[Hkv, n])."""
+    its INT2 key treatment, Sec. 3.2.1).  Tokens are generated in chunks, each
+    from its own spawned seed, so the result does not depend on the number of
+    worker threads.  Returns (K, V, outlier_idx[Hkv, n])."""
+    from concurrent.futures import ThreadPoolExecutor
     s_k, s_v, s_o = seed_seq.spawn(3)
     rng_o = np.random.default_rng(s_o)
     idx = np.stack([rng_o.choice(HEAD_DIM, outlier_channels, replace=False) for _ in range(n_kv_heads)]) \
         if outlier_channels else np.zeros((n_kv_heads, 0), np.int64)
+    mult = np.ones((n_kv_heads, HEAD_DIM), np.float32)
+    for h in range(n_kv_heads):
+        mult[h, idx[h]] = outlier_scale
+    n_chunks = max(1, -(-n_tokens // chunk_tokens))
     out = []
     for s in (s_k, s_v):
-        rng = np.random.default_rng(s)
-        n = n_tokens * n_kv_heads * HEAD_DIM
-        buf = np.empty(n, np.uint16)
-        chunk_tok = max(1, (1 << 24) // (n_kv_heads * HEAD_DIM))
-        for t0 in range(0, n_tokens, chunk_tok):
-            t1 = min(n_tokens, t0 + chunk_tok)
-            x = rng.standard_normal((t1 - t0, n_kv_heads, HEAD_DIM), dtype=np.float32)
-            for h in range(n_kv_heads):
-                x[:, h, idx[h]] *= np.float32(outlier_scale)
-            buf[t0 * n_kv_heads * HEAD_DIM:t1 * n_kv_heads * HEAD_DIM] = f32_to_bf16_bits(x).ravel()
-        out.append(buf.reshape(n_tokens, n_kv_heads, HEAD_DIM))
+        buf = np.empty((n_tokens, n_kv_heads, HEAD_DIM), np.uint16)
+        seeds = s.spawn(n_chunks)
+
+        def fill(i):
+            t0, t1 = i * chunk_tokens, min(n_tokens, (i + 1) * chunk_tokens)
+            x = np.random.default_rng(seeds[i]).standard_normal((t1 - t0, n_kv_heads, HEAD_DIM), dtype=np.float32)
+            x *= mult
+            buf[t0:t1] = f32_to_bf16_bits(x)
+
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(fill, range(n_chunks)))
+        out.append(buf)
     return out[0], out[1], idx
 
 

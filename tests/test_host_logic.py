@@ -226,3 +226,19 @@ def test_device_entry_points_validate_before_launch():
     assert call(wsb=C.c_size_t(need - 1)) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
     assert call(batch=0) == tkv.TKV_OK
     assert tkv.strerror(tkv.TKV_ERR_WORKSPACE_TOO_SMALL) == "workspace too small"
+
+
+def test_split_and_reduce_entry_points_validate_before_launch():
+    L = tkv.lib()
+    d = tkv.tkv_desc.make(8, 4, 4)
+    fake, null = C.c_void_p(0x1000), C.c_void_p(None)
+    big = C.c_size_t(1 << 30)
+    sm = C.c_float(0.088)
+    ok_args = [fake] * 9
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 4, 2, 60, sm, fake, big, null, null) == tkv.TKV_ERR_BAD_SHAPE
+    assert L.tkv_decode_split(C.byref(d), null, *ok_args[:8], 4, 2, 64, sm, fake, big, null, null) == tkv.TKV_ERR_INVALID_ARG
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 4, 2, 64, sm, fake, C.c_size_t(16), null, null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 0, 2, 64, sm, fake, big, null, null) == tkv.TKV_OK   # no items: nothing to do
+    assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, null, fake, big, null) == tkv.TKV_ERR_INVALID_ARG
+    assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, fake, fake, C.c_size_t(16), null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
+    assert L.tkv_decode_reduce(C.byref(d), fake, 4, 0, 64, fake, fake, big, null) == tkv.TKV_OK
