@@ -235,10 +235,10 @@ def test_split_and_reduce_entry_points_validate_before_launch():
     big = C.c_size_t(1 << 30)
     sm = C.c_float(0.088)
     ok_args = [fake] * 9
-    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 4, 2, 60, sm, fake, big, null, null) == tkv.TKV_ERR_BAD_SHAPE
-    assert L.tkv_decode_split(C.byref(d), null, *ok_args[:8], 4, 2, 64, sm, fake, big, null, null) == tkv.TKV_ERR_INVALID_ARG
-    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 4, 2, 64, sm, fake, C.c_size_t(16), null, null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
-    assert L.tkv_decode_split(C.byref(d), *ok_args[:9], 0, 2, 64, sm, fake, big, null, null) == tkv.TKV_OK   # no items: nothing to do
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:8], 4, 2, 60, sm, fake, big, null, null) == tkv.TKV_ERR_BAD_SHAPE
+    assert L.tkv_decode_split(C.byref(d), null, *ok_args[:7], 4, 2, 64, sm, fake, big, null, null) == tkv.TKV_ERR_INVALID_ARG
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:8], 4, 2, 64, sm, fake, C.c_size_t(16), null, null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
+    assert L.tkv_decode_split(C.byref(d), *ok_args[:8], 0, 2, 64, sm, fake, big, null, null) == tkv.TKV_OK   # no items: nothing to do
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, null, fake, big, null) == tkv.TKV_ERR_INVALID_ARG
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, fake, fake, C.c_size_t(16), null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 0, 64, fake, fake, big, null) == tkv.TKV_OK
