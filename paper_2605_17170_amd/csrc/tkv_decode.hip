@@ -42,9 +42,6 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
-#ifndef TKV_PREFETCH
-#define TKV_PREFETCH 1
-#endif
 #ifndef TKV_WAVES_PER_EU
 #define TKV_WAVES_PER_EU 2
 #endif
@@ -183,7 +180,7 @@ __device__ __forceinline__ void load_page(PageRegs<BITS> &pr, const uint8_t *__r
     pr.bm = bit_map[page];
 }
 
-template <int BITS, bool PARTIAL>
+template <int BITS>
 __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_valid, int lane,
                                              const QOperand &qo, half8 qz, float F, float kappa,
                                              float negk, WaveState &st, Lds &lds)
@@ -193,12 +190,18 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     // ---- stage metadata in LDS --------------------------------------------
     __syncthreads();   // previous page's readers are done
     {
+        // Tokens at or beyond n_valid (never-written slots of a partly filled page) are masked by count,
+        // never by content: their K scale and K zero become 0 and -inf is added to their logits below;
+        // their V scale and V zero become 0 (their P is 0, the product must not be NaN).  Full pages
+        // run the same instructions with all-ones masks.
         uint2 vsc = pr.vsc, vzc = pr.vzc;
         const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
-        reinterpret_cast<float4 *>(lds.ks)[lane] =
-            make_float4((float)a[0] * F, (float)a[1] * F, (float)b[0] * F, (float)b[1] * F);
+        const float fk = lane < n_valid ? F : 0.0f;
+        reinterpret_cast<float4 *>(lds.ks)[lane] = lane < n_valid
+            ? make_float4((float)a[0] * fk, (float)a[1] * fk, (float)b[0] * fk, (float)b[1] * fk)
+            : make_float4(0.f, 0.f, 0.f, 0.f);
         // this lane holds plane entries 4*lane .. 4*lane+3: chunk lane/2, slots 4*(lane&1) + 0..3
-        if (PARTIAL) {
+        {
             const int chunk = lane >> 1, blk = chunk >> 4, quad = (chunk >> 2) & 3, jb = 4 * (lane & 1);
             const int t0 = 32 * blk + 16 * (jb >> 2) + 4 * quad;   // tokens t0 .. t0+3
             const uint32_t m01 = (t0 < n_valid ? 0xffffu : 0u) | (t0 + 1 < n_valid ? 0xffff0000u : 0u);
@@ -227,7 +230,11 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     floatx4 S[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const half8 za = as_half8(pr.kz[e].x, pr.kz[e].y, pr.kz[e].x, pr.kz[e].y);
+        // zero-point term; slot 4 of channel-slice 1 carries the token's mask bias (0 or -inf) against a 1.0 in q's operand
+        const bool tok_ok = 16 * e + r16 < n_valid;
+        const uint32_t z01 = tok_ok ? pr.kz[e].x : 0u, z23 = tok_ok ? pr.kz[e].y : 0u;
+        const uint32_t biased = (z01 & 0xffff0000u) | (tok_ok ? 0u : 0xfc00u);
+        const half8 za = as_half8(z01, z23, q4 == 1 ? biased : z01, z23);
         floatx4 s = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});
         float4 sc[4];
 #pragma unroll
@@ -251,10 +258,6 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
                 s[i] = fmaf(scg, p[i], s[i]);
             }
         }
-        if (PARTIAL)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (16 * e + 4 * q4 + i >= n_valid) s[i] = -INFINITY;
         S[e] = s;
     }
 
@@ -340,8 +343,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     }
 }
 
-// All pages [pb, pe) of one width (indices into the sequence's page list).  Loads of the next page
-// are issued before the current page is computed.
+// All pages [pb, pe) of one width (indices into the sequence's page list).
 template <int BITS>
 __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map,
                                           const int32_t *__restrict__ pages, int pb, int pe, int last_index,
@@ -349,48 +351,36 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
                                           int n_kv_heads, int n_pages_int2, int lane, const QOperand &qo, half8 qz,
                                           float F, float kappa, float negk, WaveState &st, Lds &lds, int32_t *status)
 {
-    // a page id outside its pool cannot be addressed: it is flagged, replaced by a valid page and masked out
-    auto fetch = [&](int pi, int &page, bool &ok) {
-        page = pages[pi];
-        ok = page >= page_lo && page < page_hi;
+    // Issue the loads of list position pi into pr and return its number of valid tokens.  A page id
+    // outside its pool cannot be addressed: it is flagged, a valid page is read instead and masked out.
+    auto fetch = [&](int pi, PageRegs<BITS> &pr) -> int {
+        int page = __builtin_amdgcn_readfirstlane(pages[pi]);
+        const bool ok = page >= page_lo && page < page_hi;
         if (!ok) {
             if (status && lane == 0)
                 atomicOr(status, page < 0 || page >= n_pages_total ? TKV_STATUS_PAGE_RANGE : TKV_STATUS_BITMAP_MISMATCH);
             page = page_lo;
         }
+        load_page<BITS>(pr, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
+        return ok ? (pi == last_index ? last_valid : kPageTokens) : 0;
     };
-    int page;
-    bool ok;
-    fetch(pb, page, ok);
-    PageRegs<BITS> cur;
-#if TKV_PREFETCH
-    PageRegs<BITS> nxt;
-    load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
-    nxt = cur;
-#endif
-    for (int pi = pb; pi < pe; ++pi) {
-#if TKV_PREFETCH
-        const bool cur_ok = ok;
-        if (pi + 1 < pe) {
-            fetch(pi + 1, page, ok);
-            load_page<BITS>(nxt, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
-        }
-#else
-        if (pi > pb) fetch(pi, page, ok);
-        const bool cur_ok = ok;
-        load_page<BITS>(cur, pool + record_offset(page, kvh, n_kv_heads, n_pages_int2), bit_map, page, lane);
-#endif
-        int nv = pi == last_index ? last_valid : kPageTokens;
-        if (cur.bm != BITS && cur_ok) {
+    // the bit_map entry arrives with the page: a mismatch masks the whole page
+    auto step = [&](const PageRegs<BITS> &pr, int nv) {
+        if (pr.bm != BITS && nv > 0) {
             if (status && lane == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
             nv = 0;
         }
-        if (!cur_ok) nv = 0;
-        if (nv == kPageTokens) compute_page<BITS, false>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
-        else compute_page<BITS, true>(cur, nv, lane, qo, qz, F, kappa, negk, st, lds);
-#if TKV_PREFETCH
+        compute_page<BITS>(pr, nv, lane, qo, qz, F, kappa, negk, st, lds);
+    };
+    // Two register sets: while one page is computed the loads of the next are in flight.
+    PageRegs<BITS> cur, nxt;
+    int nv = fetch(pb, cur), nv_next = 0;
+    nxt = cur;
+    for (int pi = pb; pi < pe; ++pi) {
+        if (pi + 1 < pe) nv_next = fetch(pi + 1, nxt);
+        step(cur, nv);
         cur = nxt;
-#endif
+        nv = nv_next;
     }
 }
 
@@ -451,6 +441,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
             if (q4 == 0) { pc[g] = (float)hi; pc[4 + g] = (float)mid; }
             else if (q4 == 1) { pc[g] = (float)lo; }
         }
+        if (q4 == 1) pc[4] = 1.0f;   // multiplies the mask bias of the token rows
         qz = as_half8(pack_h2(pc[0], pc[1]), pack_h2(pc[2], pc[3]), pack_h2(pc[4], pc[5]), pack_h2(pc[6], pc[7]));
     }
 
@@ -465,12 +456,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     // INT2 pages of the range, then INT4 pages: each page runs one dequantisation path
     const int e2 = pe < np2 ? pe : np2;
     if (pb < e2) {
+        asm volatile("" ::: "memory");   // re-read q from LDS here instead of holding 128 values in registers
         build_q_operand<2>(qf[hcol], q4, two_e, qo);
         run_pages<2>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
                      n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qo, qz, F, kappa, negk, st, lds, status);
     }
     const int b4 = pb > np2 ? pb : np2;
     if (b4 < pe) {
+        asm volatile("" ::: "memory");
         build_q_operand<4>(qf[hcol], q4, two_e, qo);
         run_pages<4>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
                      n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qo, qz, F, kappa, negk, st, lds,
