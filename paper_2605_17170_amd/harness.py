@@ -124,8 +124,8 @@ class PagedCache:
 
 def default_target_items(n_kv_heads: int, device=None) -> int:
     """Work items over the batch: one wavefront serves one (item, kv head), and
-    the decode kernel's register footprint lets two wavefronts share a SIMD,
-    so 8 per compute unit fill the device in a single round."""
+    the decode kernel's register footprint lets three wavefronts share a SIMD,
+    so 12 per compute unit fill the device in a single round."""
     props = torch.cuda.get_device_properties(device if device is not None else torch.cuda.current_device())
-    waves = props.multi_processor_count * 4 * 2
+    waves = props.multi_processor_count * 4 * 3
     return max(1, waves // n_kv_heads)
