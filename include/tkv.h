@@ -169,8 +169,8 @@ int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
  * The decode kernel follows the flash-decoding design: the KV of a sequence
  * is processed as parallel contiguous splits merged by log-sum-exp
  * (Sec. 3.2.3, "Decode").  A work item is a contiguous range of one
- * sequence's page list (INT2 pages first).  Items are balanced by bytes: an
- * INT2 page weighs 3, an INT4 page 5.
+ * sequence's page list (INT2 pages first).  Items are balanced by decode cost:
+ * an INT2 page weighs 6, an INT4 page 7 (measured kernel time per page).
  *   page_indptr   host i32[batch+1], page-list offsets of the sequences
  *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial)
  *   target_items  wanted number of items over the whole batch (>= 1)

@@ -56,8 +56,8 @@ constexpr float kTau = 4.0f;   // rescale when a logit exceeds the reference max
 // Softmax weights are carried as W = P * 2^kPExp (P <= 2^kTau), so that the lo piece of a small weight
 // stays clear of the fp16 subnormal grid; numerator and denominator share the factor.
 constexpr int kPExp = 8;
-// The V scale is staged as scale * 2^kVExp (INT2 pages; INT4 pages carry 2^2 more, their codes 2^-2 less); undone once in the epilogue.
-constexpr int kVExp = -4;
+// The V scale is staged as scale * 2^(kVExp - pos), pos = bit position of the code's field in its fp16 half; undone once in the epilogue.
+constexpr int kVExp = -1;
 // W * staged scale must stay finite in fp16: the staged scale is clamped to 65504 / 2^(kTau + kPExp)
 constexpr uint32_t kVsClamp = 0x4bff4bffu;   // fp16 15.99 twice
 
@@ -137,7 +137,7 @@ struct WaveState {
 
 struct alignas(16) Lds {
     alignas(16) float ks[kPageTokens * kGroups];         // K scale * F, fp32 [token][group]
-    alignas(16) uint32_t vs[kPageTokens * kGroups / 2];  // V scale * 2^kVExp (+2 for INT4), fp16 pairs in plane order
+    alignas(16) uint32_t vs[kPageTokens * kGroups / 2];  // V scale * 2^(kVExp - pos), fp16 pairs in plane order
     alignas(16) uint32_t vz[kPageTokens * kGroups / 2];  // V zero, fp16 pairs in plane order
     alignas(16) uint2 kz[kPageTokens];                   // K zero, four fp16 per token
     alignas(16) uint4 qo[kGroups][64];                   // B operand of the QK^T MFMAs per group and lane
@@ -279,11 +279,15 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             const uint4 qb = lds.qo[g][lane];
             const half8 b = as_half8(qb.x, qb.y, qb.z, qb.w);
             const floatx4 p = mfma(a, b, floatx4{0.f, 0.f, 0.f, 0.f});
+#ifdef TKV_ABL_NOKS
+            s += p;
+#else
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float scg = g == 0 ? sc[i].x : g == 1 ? sc[i].y : g == 2 ? sc[i].z : sc[i].w;
                 s[i] = fmaf(scg, p[i], s[i]);
             }
+#endif
         }
         asm volatile("" : "+v"(s));   // the scaled sums are formed here, not sunk next to their first use
         S[e] = s;
@@ -352,8 +356,12 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 // hi rows: fp16(P_hi * scale); lo rows: P_lo * scale + (P_hi * scale - fp16(P_hi * scale))
+#ifdef TKV_ABL_NOW
+                ar[k] = pa[blk][k] ^ vsr[k];
+#else
                 const uint32_t t = pk_mul(py[blk][k], vsr[k]);
                 ar[k] = pk_fma(pa[blk][k], vsr[k], pk_rem(py[blk][k], vsr[k], t));
+#endif
             }
             const half8 a = as_half8(ar[0], ar[1], ar[2], ar[3]);
 #pragma unroll
@@ -364,19 +372,24 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
                     const uint4 v = BITS == 4 ? pr.vw[blk * 2 + (jt >> 2)] : pr.vw[jt >> 2];
                     w = (jt & 3) == 0 ? v.x : (jt & 3) == 1 ? v.y : (jt & 3) == 2 ? v.z : v.w;
                 }
-                // codes as fp16 subnormals with their field at the top of the mantissa (bits 9:6 / 9:8): the
-                // matrix core aligns the products of a lane's eight k-slots to the largest exponent *field*
-                // and drops what falls below a fixed window, so leading zeros of a subnormal cost precision
+                // Codes as fp16 subnormals, fields shifted towards the top of the mantissa (INT2: bits 4:3,
+                // 6:5, 8:7, 10:9 of each half; INT4: bits 6:3 and 10:7): the matrix core aligns the products of
+                // a lane's eight k-slots to the largest exponent *field* and drops what falls below a fixed
+                // window, so leading zeros of a subnormal cost precision.  Bit 10 is the lowest exponent bit:
+                // fp16 is linear through the first binade, so a field may reach it.  The slot's power of two
+                // is undone in the staged V scale.
                 half8 b;
+#ifdef TKV_ABL_NOSH
+                if (true) {
+                    b = as_half8(w & 0x03c003c0u, w & 0x003c003cu, w & 0x3c003c00u, w & 0x0c030c03u);
+                } else
+#endif
                 if (BITS == 4) {
-                    b = as_half8((w << 6) & 0x03c003c0u, (w << 2) & 0x03c003c0u, (w >> 2) & 0x03c003c0u,
-                                 (w >> 6) & 0x03c003c0u);
-                } else if (blk == 0) {
-                    b = as_half8((w << 8) & 0x03000300u, (w << 6) & 0x03000300u, (w << 4) & 0x03000300u,
-                                 (w << 2) & 0x03000300u);
+                    const uint32_t wl = w << 3, wr = w >> 5;
+                    b = as_half8(wl & 0x00780078u, wl & 0x07800780u, wr & 0x00780078u, wr & 0x07800780u);
                 } else {
-                    b = as_half8(w & 0x03000300u, (w >> 2) & 0x03000300u, (w >> 4) & 0x03000300u,
-                                 (w >> 6) & 0x03000300u);
+                    const uint32_t ws = blk ? (w >> 5) : (w << 3);
+                    b = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
                 }
                 st.acc[jt] = mfma(a, b, st.acc[jt]);
             }
@@ -390,13 +403,18 @@ template <int BITS>
 __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map,
                                           const int32_t *__restrict__ pages, int pb, int pe, int last_index,
                                           int last_valid, int page_lo, int page_hi, int n_pages_total, int kvh,
-                                          int n_kv_heads, int n_pages_int2, int lane, half8 qz,
+                                          int n_kv_heads, int n_pages_int2, int item_end, int item_pages, int lane, half8 qz,
                                           LaneConst lc, WaveState &st, Lds &lds, int32_t *status)
 {
-    // the V codes enter the MFMA as code * 2^-18 (INT4) or code * 2^-16 (INT2): stage the scale with the difference
+    // A V code enters the MFMA as code * 2^(pos - 24), pos = lowest bit of its field after the unpack shift; the
+    // staged scale of the slot carries 2^(kVExp - pos).  This lane stages plane entries 4*lane .. 4*lane+3 =
+    // k-slots 4*(lane&1) + 0..3, i.e. operand registers 2*(lane&1) (first pair) and 2*(lane&1) + 1 (second pair).
     {
-        const uint32_t h = (uint32_t)(15 + kVExp + (BITS == 4 ? 2 : 0)) << 10;
-        lc.vmul01 = lc.vmul23 = h | (h << 16);
+        const int k0 = 2 * (lane & 1);
+        const int p01 = BITS == 4 ? 3 : 3 + 2 * k0, p23 = BITS == 4 ? 7 : 5 + 2 * k0;
+        const uint32_t h01 = (uint32_t)(15 + kVExp - p01) << 10, h23 = (uint32_t)(15 + kVExp - p23) << 10;
+        lc.vmul01 = h01 | (h01 << 16);
+        lc.vmul23 = h23 | (h23 << 16);
     }
     // Page id of list position pi and its number of valid tokens.  A page id outside its pool cannot be
     // addressed: it is flagged, a valid page is read instead and skipped.
@@ -421,7 +439,19 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
     const uint8_t *rec = pool + record_offset(page, kvh, n_kv_heads, n_pages_int2);
     load_page_a<BITS>(pr, rec, bit_map, page, lane);
     load_page_b<BITS>(pr, rec, lane);
+    int quartile = -1;
     for (int pi = pb; pi < pe; ++pi) {
+        // Wavefronts that share a SIMD are served oldest first; left alone, the oldest finishes long before
+        // the others and the SIMD ends its work with one wavefront.  The priority follows the share of the
+        // item still to do, so the wavefronts of a SIMD advance together.
+        const int q = (4 * (item_end - pi) - 1) / item_pages;   // 3 .. 0
+        if (__builtin_expect(q != quartile, 0)) {
+            quartile = q;
+            if (q >= 3) __builtin_amdgcn_s_setprio(3);
+            else if (q == 2) __builtin_amdgcn_s_setprio(2);
+            else if (q == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         // the last page requests its own record again: no branch around the loads
         const int pi_next = pi + 1 < pe ? pi + 1 : pi;
         const uint8_t *rec_next = rec;
@@ -546,14 +576,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
         build_q_operand<2>(qf[hcol], q4, lane, lds);
         lds_order();
         run_pages<2>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
-                     n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qz, lc, st, lds, status);
+                     n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
     }
     const int b4 = pb > np2 ? pb : np2;
     if (b4 < pe) {
         build_q_operand<4>(qf[hcol], q4, lane, lds);
         lds_order();
         run_pages<4>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
-                     n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, lane, qz, lc, st, lds, status);
+                     n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
     }
 
 #ifdef TKV_TRACE
@@ -573,7 +603,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
         for (int i = 0; i < 4; ++i) lds.zl[4 * q4 + i][r16] = st.zacc[i];   // [head][column]
     if (q4 == 0 && r16 < 8) lds.alpha[r16] = st.m_ref;
     lds_order();
-    const float unscale = ldexpf(1.0f, 16 - kVExp);
+    const float unscale = ldexpf(1.0f, 24 - kVExp);
     if (q4 < 2) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

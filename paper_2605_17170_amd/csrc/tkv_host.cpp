@@ -301,7 +301,9 @@ int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page
     if (batch < 0 || target_items < 1 || capacity < 0 || !page_indptr || !seq_item_indptr_out) return TKV_ERR_INVALID_ARG;
     if (batch > 0 && (!n_tok_int2 || !n_tok_int4)) return TKV_ERR_INVALID_ARG;
     if (capacity > 0 && !items_out) return TKV_ERR_INVALID_ARG;
-    constexpr int64_t kCost2 = 3, kCost4 = 5;   // bytes of an INT2 : INT4 record = 6144 : 10240
+    // decode cost of a page: the kernel is bound by instruction issue, not bytes, and an INT4 page costs
+    // about 7/6 of an INT2 page (same MFMA count, a few more unpack operations, more bytes in flight)
+    constexpr int64_t kCost2 = 6, kCost4 = 7;
     int64_t total = 0;
     for (int32_t b = 0; b < batch; ++b) {
         if (n_tok_int2[b] < 0 || n_tok_int4[b] < 0) return TKV_ERR_INVALID_ARG;

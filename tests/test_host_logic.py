@@ -160,8 +160,8 @@ def test_plan_decode_covers_every_page_once_and_balances_bytes(target):
     items, sip = tkv.tkv_plan_decode(d, ip, n2, n4, target)
     assert sip[0] == 0 and sip[-1] == items.shape[0] and np.all(np.diff(sip) >= 0)
     assert items.shape[0] <= tkv.tkv_plan_decode_capacity(B, target)
-    cost = lambda b, lo, hi: 3 * (min(hi, -(-n2[b] // 64)) - min(lo, -(-n2[b] // 64))) + \
-        5 * (max(hi, -(-n2[b] // 64)) - max(lo, -(-n2[b] // 64)))
+    cost = lambda b, lo, hi: 6 * (min(hi, -(-n2[b] // 64)) - min(lo, -(-n2[b] // 64))) + \
+        7 * (max(hi, -(-n2[b] // 64)) - max(lo, -(-n2[b] // 64)))
     costs = []
     for b in range(B):
         its = items[sip[b]:sip[b + 1]]
@@ -172,7 +172,7 @@ def test_plan_decode_covers_every_page_once_and_balances_bytes(target):
         assert its[0, 1] == 0 and its[-1, 2] == pages[b]
         assert np.all(its[1:, 1] == its[:-1, 2]) and np.all(its[:, 2] > its[:, 1])
         costs += [cost(b, lo, hi) for _, lo, hi, _ in its]
-    total = sum(3 * -(-int(a) // 64) + 5 * -(-int(b) // 64) for a, b in zip(n2, n4))
+    total = sum(6 * -(-int(a) // 64) + 7 * -(-int(b) // 64) for a, b in zip(n2, n4))
     assert sum(costs) == total
     if target >= 64:
         per = total / target
