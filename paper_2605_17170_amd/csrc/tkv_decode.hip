@@ -279,15 +279,11 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             const uint4 qb = lds.qo[g][lane];
             const half8 b = as_half8(qb.x, qb.y, qb.z, qb.w);
             const floatx4 p = mfma(a, b, floatx4{0.f, 0.f, 0.f, 0.f});
-#ifdef TKV_ABL_NOKS
-            s += p;
-#else
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float scg = g == 0 ? sc[i].x : g == 1 ? sc[i].y : g == 2 ? sc[i].z : sc[i].w;
                 s[i] = fmaf(scg, p[i], s[i]);
             }
-#endif
         }
         asm volatile("" : "+v"(s));   // the scaled sums are formed here, not sunk next to their first use
         S[e] = s;
@@ -356,12 +352,8 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 // hi rows: fp16(P_hi * scale); lo rows: P_lo * scale + (P_hi * scale - fp16(P_hi * scale))
-#ifdef TKV_ABL_NOW
-                ar[k] = pa[blk][k] ^ vsr[k];
-#else
                 const uint32_t t = pk_mul(py[blk][k], vsr[k]);
                 ar[k] = pk_fma(pa[blk][k], vsr[k], pk_rem(py[blk][k], vsr[k], t));
-#endif
             }
             const half8 a = as_half8(ar[0], ar[1], ar[2], ar[3]);
 #pragma unroll
@@ -379,11 +371,6 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
                 // fp16 is linear through the first binade, so a field may reach it.  The slot's power of two
                 // is undone in the staged V scale.
                 half8 b;
-#ifdef TKV_ABL_NOSH
-                if (true) {
-                    b = as_half8(w & 0x03c003c0u, w & 0x003c003cu, w & 0x3c003c00u, w & 0x0c030c03u);
-                } else
-#endif
                 if (BITS == 4) {
                     const uint32_t wl = w << 3, wr = w >> 5;
                     b = as_half8(wl & 0x00780078u, wl & 0x07800780u, wr & 0x00780078u, wr & 0x07800780u);
@@ -420,9 +407,6 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
     // addressed: it is flagged, a valid page is read instead and skipped.
     auto resolve = [&](int pi, int &page) -> int {
         page = __builtin_amdgcn_readfirstlane(pages[pi]);
-#ifdef TKV_SAMEPAGE
-        page = page_lo + (page & 63);   // timing experiment: every record comes from the caches
-#endif
         const bool ok = page >= page_lo && page < page_hi;
         if (!ok) {
             if (status && lane == 0)
@@ -484,14 +468,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     const int32_t *__restrict__ n_tok_int2, const int32_t *__restrict__ n_tok_int4,
     const int32_t *__restrict__ items, int batch, int n_kv_heads, int n_q_heads, int n_pages_int2, int n_pages_int4,
     float kappa, float *__restrict__ acc_ws, float *__restrict__ ml_ws, int32_t *status
-#ifdef TKV_TRACE
-    , unsigned long long *trace
-#endif
     )
 {
-#ifdef TKV_TRACE
-    const unsigned long long t_start = wall_clock64();
-#endif
     __shared__ Lds lds;
     __shared__ float qf[8][kHeadDim];
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
@@ -586,9 +564,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
                      n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
     }
 
-#ifdef TKV_TRACE
-    const unsigned long long t_loop = wall_clock64();
-#endif
     // ---- write the partial (m, l, acc) of this item ------------------------------
     // rows 0..7 carry the hi piece of P, rows 8..15 the lo piece: add lanes l and l^32
 #pragma unroll
@@ -619,15 +594,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
             }
         }
     }
-#ifdef TKV_TRACE
-    if (lane == 0) {
-        trace[4 * blockIdx.x] = t_start;
-        trace[4 * blockIdx.x + 1] = t_loop;
-        trace[4 * blockIdx.x + 2] = wall_clock64();
-        trace[4 * blockIdx.x + 3] = (unsigned long long)__builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)) |
-                                    ((unsigned long long)__builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11)) << 32);
-    }
-#endif
 }
 
 // D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence.
@@ -696,9 +662,6 @@ int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_
                        (hipStream_t)stream, (const uint8_t *)pool, bit_map, (const uint16_t *)q, page_indptr,
                        page_ids, n_tok_int2, n_tok_int4, items, batch, desc->n_kv_heads, n_q_heads,
                        desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status
-#ifdef TKV_TRACE
-                       , (unsigned long long *)(ml_ws + (size_t)n_items * n_q_heads * 2)
-#endif
                        );
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
 }
