@@ -204,6 +204,9 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
  *   out            device fp32 [batch, n_q_heads, head_dim]
  *   workspace      device, >= tkv_decode_workspace_bytes(...), 16-byte aligned
  *   status         device i32, may be NULL
+ * Preconditions on the cache contents (not checked): stored scales and zeros
+ * finite; V scales up to 255 are used exactly, larger ones saturate at 255
+ * (the kernel forms softmax weight x V scale in fp16 and keeps it finite).
  * n_q_heads / n_kv_heads must be 1, 2, 4 or 8.  Two launches on `stream`:
  * the split kernel, then the cross-split reduction.
  */
