@@ -16,6 +16,9 @@
  *     an offset (Sec. 3.2.1 "Buffer layout", Sec. 3.2.2 "Shared address
  *     space"); the byte order inside a page follows this build's own layout
  *     specification, re-implemented here from its formulas;
+ *   - the prefill gather (Sec. 3.2.3 "Prefill"): the cached rows of a matched
+ *     prefix dequantised into FP16, value = binary16 nearest-even rounding of
+ *     the exact code * scale + zero (one rounding);
  *   - decode attention softmax(q K^T / sqrt(d)) V over the dequantised cache
  *     (Sec. 3.2.3 "Decode"): the flash-decoding splits and the log-sum-exp
  *     merge reach exactly this value, so the oracle is the plain definition,
@@ -31,7 +34,9 @@
  * torch casts, hand-worked groups, nearest-code brute force, the scale/2
  * round-trip bound, exactly-representable inputs against unquantised fp64
  * attention, brute force on tiny heads, closed forms, codec bijectivity and
- * hand-derived bit positions.  No function here is "parity unpinned".
+ * hand-derived bit positions; the FP16 dequantisation against numpy's
+ * float64 -> float16 cast and exact rational arithmetic.  No function here
+ * is "parity unpinned".
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
  */
@@ -96,6 +101,36 @@ uint16_t tkvo_f32_to_f16(float f)
     if (rest > half || (rest == half && (keep & 1u))) keep += 1u;
     return (uint16_t)(sign | keep);
 }
+
+/* binary64 -> binary16, round to nearest even, ONE rounding (no detour through binary32). */
+uint16_t tkvo_f64_to_f16(double d)
+{
+    uint64_t u;
+    memcpy(&u, &d, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+    uint32_t ex = (uint32_t)((u >> 52) & 0x7ffu);
+    uint64_t man = u & 0xfffffffffffffull;
+    if (ex == 2047) return (uint16_t)(sign | 0x7c00u | (man ? 0x200u : 0u));
+    if (ex == 0) return sign;           /* zero or a binary64 subnormal: far below 2^-25 */
+    int e = (int)ex - 1023;
+    if (e > 15) return (uint16_t)(sign | 0x7c00u);
+    if (e >= -14) {
+        uint32_t keep = (uint32_t)(man >> 42);
+        uint64_t rest = man & ((1ull << 42) - 1ull), half = 1ull << 41;
+        uint32_t h = ((uint32_t)(e + 15) << 10) | keep;
+        if (rest > half || (rest == half && (keep & 1u))) h += 1u;   /* may carry into the exponent / to inf */
+        return (uint16_t)(sign | h);
+    }
+    if (e < -25) return sign;
+    uint64_t full = man | (1ull << 52);  /* value full * 2^(e-52) = m * 2^-24 with m = full * 2^(e-28) */
+    int shift = 28 - e;                  /* 42..53 */
+    uint64_t keep = full >> shift;
+    uint64_t rest = full & ((1ull << shift) - 1ull), half = 1ull << (shift - 1);
+    if (rest > half || (rest == half && (keep & 1ull))) keep += 1ull;
+    return (uint16_t)(sign | (uint16_t)keep);
+}
+void tkvo_f64_to_f16_array(const double *in, uint16_t *out, int64_t n)
+{ for (int64_t i = 0; i < n; ++i) out[i] = tkvo_f64_to_f16(in[i]); }
 
 void tkvo_bf16_to_f32_array(const uint16_t *in, float *out, int64_t n)
 { for (int64_t i = 0; i < n; ++i) out[i] = tkvo_bf16_to_f32(in[i]); }
@@ -172,6 +207,22 @@ void tkvo_dequantize(const uint8_t *codes, const uint16_t *scale, const uint16_t
             double s = (double)tkvo_f16_to_f32(scale[th * NG + c / G]);
             double z = (double)tkvo_f16_to_f32(zero[th * NG + c / G]);
             out[th * D + c] = (double)codes[th * D + c] * s + z;
+        }
+}
+
+/* Prefill gather (Sec. 3.2.3 "Prefill"): the cached rows dequantised into FP16.  code * scale has at most
+ * 15 significant bits and both terms lie on the binary16 exponent range, so the binary64 sum below is the
+ * exact value; it is rounded to binary16 once. */
+void tkvo_dequantize_f16(const uint8_t *codes, const uint16_t *scale, const uint16_t *zero,
+                         int64_t T, int H, int D, int G, uint16_t *out)
+{
+    const int NG = D / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t th = 0; th < T * H; ++th)
+        for (int c = 0; c < D; ++c) {
+            double s = (double)tkvo_f16_to_f32(scale[th * NG + c / G]);
+            double z = (double)tkvo_f16_to_f32(zero[th * NG + c / G]);
+            out[th * D + c] = tkvo_f64_to_f16((double)codes[th * D + c] * s + z);
         }
 }
 

@@ -89,6 +89,14 @@ def f32_to_f16(x_f32):
 
 
 # ---------------------------------------------------------------- quantiser
+def f64_to_f16(x_f64):
+    """binary64 -> binary16 bit patterns, nearest-even, one rounding."""
+    x = _c(x_f64, np.float64)
+    out = np.empty(x.shape, np.uint16)
+    lib().tkvo_f64_to_f16_array(_p(x), _p(out), C.c_int64(x.size))
+    return out
+
+
 def quantize_group(x_u16, bits: int):
     """One group of G channels -> (codes u8[G], scale u16, zero u16)."""
     x = _c(x_u16, np.uint16)
@@ -127,6 +135,18 @@ def dequantize(codes, scale, zero, G: int = GS):
 
 
 # ---------------------------------------------------------------- attention
+def dequantize_f16(codes, scale, zero, G: int = GS):
+    """The cached rows as FP16 bit patterns [T,H,D] (Sec. 3.2.3 "Prefill"): nearest-even of the exact
+    code * scale + zero."""
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    T, H, D = codes.shape
+    out = np.empty((T, H, D), np.uint16)
+    lib().tkvo_dequantize_f16(_p(codes), _p(scale), _p(zero), C.c_int64(T), C.c_int(H), C.c_int(D), C.c_int(G), _p(out))
+    return out
+
+
 def attention_f64(q, K, V, seq_indptr, sm_scale: float):
     """Plain fp64 softmax(q K^T * sm_scale) V with grouped-query heads.
     q [B,Hq,D] f64; K,V [T,Hkv,D] f64; seq_indptr i64 [B+1]."""
