@@ -127,6 +127,15 @@ def main():
     app_write = cache.kv_bytes()
     assert int(cache.status.item()) == 0
 
+    # ---- prefill gather leg (dequantises the whole cached context back into fp16 rows)
+    gK = torch.empty((w.n_tokens, w.n_kv_heads, 128), dtype=torch.float16, device=dev)
+    gV = torch.empty_like(gK)
+    gat_per, _ = time_steps(lambda i: cache.gather(gK, gV), 5, 2)
+    gat_ms = float(np.median(gat_per))
+    gat_bytes = cache.kv_bytes() + 2 * gK.numel() * 2
+    assert int(cache.status.item()) == 0
+    del gK, gV
+
     # ---- decode leg
     target = args.target_items or harness.default_target_items(w.n_kv_heads, dev)
     t0 = time.perf_counter()
@@ -177,6 +186,10 @@ def main():
                    "GBps_read_plus_write": (app_read + app_write) / (app_ms * 1e-3) / 1e9,
                    "pct_of_hbm_peak": 100.0 * (app_read + app_write) / (app_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "note": "tkv_quantize_append of the whole context (bf16 K,V read + packed pages written), outside the timed steps"},
+        "prefill_gather": {"ms": gat_ms, "tokens_per_s": w.n_tokens / (gat_ms * 1e-3),
+                           "GBps_read_plus_write": gat_bytes / (gat_ms * 1e-3) / 1e9,
+                           "pct_of_hbm_peak": 100.0 * gat_bytes / (gat_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "note": "tkv_gather_dequant of the whole context (packed pages read + fp16 K,V rows written), outside the timed steps"},
         "roofline": {"bound": "hbm", "achieved": kv_bytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": kv_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": read_traffic("decode_%s_hbm_traffic.txt" % args.config),

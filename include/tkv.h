@@ -47,7 +47,8 @@ enum {
 enum {
     TKV_STATUS_TAG_MISMATCH = 1,     /* append: tag_bits[token] differs from its page's pool width (token skipped) */
     TKV_STATUS_BITMAP_MISMATCH = 2,  /* decode: bit_map[page] differs from the width its position implies (page skipped) */
-    TKV_STATUS_PAGE_RANGE = 4        /* a page id read on the device lies outside the pool (page skipped) */
+    TKV_STATUS_PAGE_RANGE = 4,       /* a page id read on the device lies outside the pool (page skipped) */
+    TKV_STATUS_DST_RANGE = 8         /* tkv_gather_dequant: an output row index >= n_tokens (slot skipped) */
 };
 
 const char *tkv_strerror(int status);
@@ -161,6 +162,33 @@ int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
                         int32_t n_tokens, int32_t group_size,
                         const int32_t *work_pages, const int32_t *work_src, int32_t n_work,
                         int32_t *status, void *stream /* hipStream_t */);
+
+/* ------------------------------------------------------------------ */
+/* P1: prefill gather-dequant (device).                                 */
+/* ------------------------------------------------------------------ */
+/*
+ * Reads the listed pages of a matched prefix from the pool, unpacks every
+ * listed slot, dequantises it into FP16 and writes dense K / V rows for an
+ * FP16 prefill attention kernel (Sec. 3.2.3, "Prefill").  Each value is the
+ * binary16 nearest-even rounding of the exact code * scale + zero.
+ *   pool, bit_map  device, as filled by tkv_quantize_append
+ *   work_pages     device i32[n_work]: the pages to read, each at most once
+ *   work_dst       device i32[n_work*64]: for each page and slot the output
+ *                  row (token index) or -1 to skip the slot; the lists that
+ *                  tkv_plan_append wrote (work_pages_out, work_src_out) name
+ *                  exactly the rows the tokens came from
+ *   K_out, V_out   device fp16 [n_tokens, n_kv_heads, head_dim], contiguous,
+ *                  16-byte aligned; rows that no slot names are left untouched
+ *   status         device i32, may be NULL: TKV_STATUS_PAGE_RANGE (page id
+ *                  outside the pool), TKV_STATUS_BITMAP_MISMATCH (page never
+ *                  written at its pool's width), TKV_STATUS_DST_RANGE; the
+ *                  page or slot concerned is skipped
+ * n_work = 0 is a no-op.
+ */
+int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                       const int32_t *work_pages, const int32_t *work_dst, int32_t n_work,
+                       void *K_out, void *V_out, int32_t n_tokens,
+                       int32_t *status, void *stream /* hipStream_t */);
 
 /* ------------------------------------------------------------------ */
 /* D1: cut page lists into work items (host).                           */

@@ -362,6 +362,19 @@ int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
     return tkv_launch_append(desc, pool, bit_map, K, V, tag_bits, n_tokens, work_pages, work_src, n_work, status, stream);
 }
 
+int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                       const int32_t *work_pages, const int32_t *work_dst, int32_t n_work,
+                       void *K_out, void *V_out, int32_t n_tokens, int32_t *status, void *stream)
+{
+    if (int st = desc_status(desc)) return st;
+    if (n_tokens < 0 || n_work < 0) return TKV_ERR_INVALID_ARG;
+    if (n_work == 0) return TKV_OK;
+    if (!pool || !bit_map || !K_out || !V_out || !work_pages || !work_dst) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)K_out & 15) || ((uintptr_t)V_out & 15)) return TKV_ERR_INVALID_ARG;
+    if ((int64_t)n_work * desc->n_kv_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_gather(desc, pool, bit_map, work_pages, work_dst, n_work, K_out, V_out, n_tokens, status, stream);
+}
+
 size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t n_q_heads)
 {
     if (!desc_ok(desc) || n_items < 0 || n_q_heads <= 0) return 0;

@@ -10,6 +10,10 @@ int tkv_launch_append(const tkv_desc *desc, void *pool, uint8_t *bit_map, const 
                       const uint8_t *tag_bits, int32_t n_tokens, const int32_t *work_pages,
                       const int32_t *work_src, int32_t n_work, int32_t *status, void *stream);
 
+int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const int32_t *work_pages,
+                      const int32_t *work_dst, int32_t n_work, void *K_out, void *V_out, int32_t n_tokens,
+                      int32_t *status, void *stream);
+
 int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
                             const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
                             const int32_t *n_tok_int4, const int32_t *items, int32_t n_items, int32_t batch,

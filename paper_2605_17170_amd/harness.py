@@ -82,6 +82,12 @@ class PagedCache:
         tkv.tkv_quantize_append(self.desc, self.pool if pool is None else pool, self.bit_map, K, V,
                                 self.d_tag_bits, self.d_work_pages, self.d_work_src, self.status, stream)
 
+    # -- P1
+    def gather(self, K_out: torch.Tensor, V_out: torch.Tensor, pool=None, stream=None):
+        """Prefill gather of every cached token back into its original row (fp16 [T,Hkv,D])."""
+        tkv.tkv_gather_dequant(self.desc, self.pool if pool is None else pool, self.bit_map, self.d_work_pages,
+                               self.d_work_src, K_out, V_out, self.status, stream)
+
     # -- D1
     def plan_decode(self, target_items: int):
         items, sip = tkv.tkv_plan_decode(self.desc, self.page_indptr, self.n_tok2, self.n_tok4, target_items)

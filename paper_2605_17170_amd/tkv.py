@@ -25,6 +25,7 @@ TKV_ERR_CAPACITY = -8
 TKV_STATUS_TAG_MISMATCH = 1
 TKV_STATUS_BITMAP_MISMATCH = 2
 TKV_STATUS_PAGE_RANGE = 4
+TKV_STATUS_DST_RANGE = 8
 
 PAGE_TOKENS = 64
 HEAD_DIM = 128
@@ -34,7 +35,7 @@ EXPORTS = [
     "tkv_strerror", "tkv_record_bytes", "tkv_page_bytes", "tkv_pool_bytes", "tkv_record_offset",
     "tkv_alloc_create", "tkv_alloc_destroy", "tkv_alloc_pages", "tkv_free_pages", "tkv_alloc_free_count",
     "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
-    "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append",
+    "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
     "tkv_decode_split", "tkv_decode_reduce",
 ]
@@ -99,6 +100,8 @@ def lib():
         L.tkv_plan_append_max_work.argtypes = [i32]
         L.tkv_plan_append.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, C.POINTER(i32)]
         L.tkv_quantize_append.argtypes = [dp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
+        L.tkv_gather_dequant.restype = C.c_int
+        L.tkv_gather_dequant.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.tkv_plan_decode_capacity.restype = i32
         L.tkv_plan_decode_capacity.argtypes = [i32, i32]
         L.tkv_plan_decode.restype = i32
@@ -254,6 +257,24 @@ def tkv_quantize_append(desc, pool, bit_map, K, V, tag_bits, work_pages, work_sr
     _check(lib().tkv_quantize_append(C.byref(desc), _dev(pool), _dev(bit_map), _dev(K), _dev(V), _dev(tag_bits),
                                      n_tokens, group_size, _dev(work_pages), _dev(work_src), n_work,
                                      _dev(status), _stream(stream)), "tkv_quantize_append")
+
+
+# ---------------------------------------------------------------- P1 (device)
+def tkv_gather_dequant(desc, pool, bit_map, work_pages, work_dst, K_out, V_out, status=None, stream=None):
+    """Prefill gather: pool u8, bit_map u8, work_pages i32[n_work], work_dst i32[n_work,64] (output row per
+    slot or -1), K_out/V_out fp16 [T,Hkv,D]; all torch device tensors."""
+    n_work = int(work_pages.numel()) if work_pages is not None else 0
+    n_tokens = int(K_out.shape[0]) if K_out is not None else 0
+    if n_work:
+        assert tuple(V_out.shape) == tuple(K_out.shape) == (n_tokens, desc.n_kv_heads, desc.head_dim)
+        assert K_out.element_size() == 2 and V_out.element_size() == 2
+        assert K_out.is_contiguous() and V_out.is_contiguous()
+        assert work_dst.numel() == n_work * desc.page_tokens and work_dst.element_size() == 4
+        assert pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
+        assert bit_map.numel() >= desc.n_pages_int2 + desc.n_pages_int4
+    _check(lib().tkv_gather_dequant(C.byref(desc), _dev(pool), _dev(bit_map), _dev(work_pages), _dev(work_dst), n_work,
+                                    _dev(K_out), _dev(V_out), n_tokens, _dev(status), _stream(stream)),
+           "tkv_gather_dequant")
 
 
 # ---------------------------------------------------------------- D1 (host)

@@ -242,3 +242,27 @@ def test_split_and_reduce_entry_points_validate_before_launch():
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, null, fake, big, null) == tkv.TKV_ERR_INVALID_ARG
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 2, 64, fake, fake, C.c_size_t(16), null) == tkv.TKV_ERR_WORKSPACE_TOO_SMALL
     assert L.tkv_decode_reduce(C.byref(d), fake, 4, 0, 64, fake, fake, big, null) == tkv.TKV_OK
+
+
+def test_gather_dequant_validates_before_launch():
+    L = tkv.lib()
+    d = tkv.tkv_desc.make(8, 4, 4)
+    buf = (C.c_uint8 * 4096)()
+    base = (C.addressof(buf) + 255) & ~255
+    p = C.c_void_p(base)
+    def call(**kw):
+        a = dict(pool=p, bm=p, wp=p, wd=p, n_work=C.c_int32(1), Ko=p, Vo=p, n_tokens=C.c_int32(64), st=None, stream=None)
+        a.update(kw)
+        return L.tkv_gather_dequant(C.byref(d), a["pool"], a["bm"], a["wp"], a["wd"], a["n_work"], a["Ko"], a["Vo"],
+                                    a["n_tokens"], a["st"], a["stream"])
+    assert call(n_work=C.c_int32(0)) == tkv.TKV_OK                       # nothing to do: no launch
+    assert call(n_work=C.c_int32(-1)) == tkv.TKV_ERR_INVALID_ARG
+    assert call(n_tokens=C.c_int32(-1)) == tkv.TKV_ERR_INVALID_ARG
+    assert call(pool=None) == tkv.TKV_ERR_INVALID_ARG
+    assert call(Ko=None) == tkv.TKV_ERR_INVALID_ARG
+    assert call(wd=None) == tkv.TKV_ERR_INVALID_ARG
+    assert call(Ko=C.c_void_p(base + 8)) == tkv.TKV_ERR_INVALID_ARG       # output rows must be 16-byte aligned
+    assert call(pool=C.c_void_p(base + 16)) == tkv.TKV_ERR_INVALID_ARG    # pool must be 256-byte aligned
+    bad = tkv.tkv_desc.make(8, 4, 4)
+    bad.head_dim = 64
+    assert L.tkv_gather_dequant(C.byref(bad), p, p, p, p, 0, p, p, 0, None, None) != tkv.TKV_OK
