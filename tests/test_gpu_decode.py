@@ -150,6 +150,27 @@ def test_large_q_and_peaked_softmax(G):
     _run(G, wl.f32_to_bf16_bits(qf), K, V, seq_bits, 8, 1, targets=(4,))
 
 
+def test_v_magnitudes_across_the_supported_range(G):
+    """The kernel multiplies the softmax weights by the V scale in fp16: V scaled by 4 (INT2 scales of
+    the outlier groups ~200, close to the documented limit of 255) and by 2^-10 (staged scales in the
+    fp16 subnormal range) must still meet the tolerance."""
+    q, K, V, seq_bits = G.random_case(22, [700, 100], 8, 1)
+    for f in (4.0, 2.0 ** -10):
+        Vs = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(V) * np.float32(f))
+        _run(G, q, K, Vs, seq_bits, 8, 1, targets=(1, 9))
+
+
+def test_v_scale_beyond_the_limit_saturates_and_stays_finite(G):
+    """Out of contract (V scale > 255): the staged scale saturates, the output is wrong but finite and
+    nothing is flagged; documents the behaviour promised in the header."""
+    q, K, V, seq_bits = G.random_case(23, [300], 8, 1)
+    Vs = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(V) * np.float32(64.0))
+    cache, _ = G.check_append(seq_bits, K, Vs, 1)
+    out = G.gpu_decode(cache, q, 3)
+    assert np.all(np.isfinite(out))
+    cache.close()
+
+
 def test_cfg1(G):
     w = wl.config("cfg1")
     q, K, V, _ = w.make_inputs()
