@@ -115,6 +115,35 @@ int32_t tkv_seq_n_pages(const tkv_seq *s, int bits);
 int32_t tkv_seq_page_ids(const tkv_seq *s, int32_t *out, int32_t capacity);
 
 /* ------------------------------------------------------------------ */
+/* A1: tag -> bitwidth allocation (host).                               */
+/* ------------------------------------------------------------------ */
+/*
+ * Chooses b_k in {2, 4} for every tag k so that the total distortion
+ * sum_k D_k(b_k) is small under the budget sum_k N_k b_k <= B sum_k N_k
+ * (Sec. 3.1.3, Eq. 3).  All arrays are host memory.
+ *   n_tags   number of tags (the paper's triaxial space has 56)
+ *   N        i64[n_tags]  token count of each tag, >= 0
+ *   D2, D4   f64[n_tags]  distortion of the tag at 2 / 4 bits, finite
+ *   B        target average bitwidth, 2 <= B <= 4
+ *   bits_out u8[n_tags]   2 or 4 per tag
+ * The budget is T = B * sum N in binary64 with a relative slack of 2^-40 (a
+ * decimal B is not a binary64 number); bits in use are counted exactly.
+ * tkv_allocate_bits_greedy is Alg. 1: per-bit gain rho_k = (D_k(2) - D_k(4)) /
+ * (2 N_k) (Eq. 4; +inf / 0 / -inf by the sign of the gain when N_k = 0), tags
+ * visited by rho descending (ties in tag order), a tag is upgraded whenever its
+ * 2 N_k extra bits still fit.  tkv_allocate_bits_exhaustive visits all 2^n_tags
+ * allocations (n_tags <= 22, as in the paper) and returns the feasible one of
+ * least total distortion; ties go to fewer total bits, then to the smaller mask
+ * (tag 0 = lowest bit, set = 4 bits).
+ * Errors: TKV_ERR_INVALID_ARG (null array, negative count, non-finite distortion,
+ * B outside [2, 4], n_tags < 0 or > 22 for the exhaustive search).
+ */
+int tkv_allocate_bits_greedy(int32_t n_tags, const int64_t *N, const double *D2, const double *D4,
+                             double B, uint8_t *bits_out);
+int tkv_allocate_bits_exhaustive(int32_t n_tags, const int64_t *N, const double *D2, const double *D4,
+                                 double B, uint8_t *bits_out);
+
+/* ------------------------------------------------------------------ */
 /* Q1: route newly arrived tokens to slots (host).                      */
 /* ------------------------------------------------------------------ */
 /* Upper bound of pages one tkv_plan_append call over n_tokens can touch. */

@@ -10,6 +10,7 @@
 #include "tkv_internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -360,6 +361,83 @@ int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
     if (((uintptr_t)pool & 255) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15)) return TKV_ERR_INVALID_ARG;
     if ((int64_t)n_work * desc->n_kv_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
     return tkv_launch_append(desc, pool, bit_map, K, V, tag_bits, n_tokens, work_pages, work_src, n_work, status, stream);
+}
+
+namespace {
+int alloc_args_status(int32_t n_tags, const int64_t *N, const double *D2, const double *D4, double B, const uint8_t *out)
+{
+    if (n_tags < 0 || !(B >= 2.0) || !(B <= 4.0)) return TKV_ERR_INVALID_ARG;
+    if (n_tags == 0) return TKV_OK;
+    if (!N || !D2 || !D4 || !out) return TKV_ERR_INVALID_ARG;
+    for (int32_t k = 0; k < n_tags; ++k)
+        if (N[k] < 0 || !std::isfinite(D2[k]) || !std::isfinite(D4[k])) return TKV_ERR_INVALID_ARG;
+    return TKV_OK;
+}
+// Largest admissible number of cache bits: B * sum N with a relative slack of 2^-40.
+double alloc_limit(int32_t n_tags, const int64_t *N, double B, int64_t *sum_out)
+{
+    int64_t sum = 0;
+    for (int32_t k = 0; k < n_tags; ++k) sum += N[k];
+    *sum_out = sum;
+    const double t = B * (double)sum;
+    return t * (1.0 + std::ldexp(1.0, -40));
+}
+} // namespace
+
+int tkv_allocate_bits_greedy(int32_t n_tags, const int64_t *N, const double *D2, const double *D4,
+                             double B, uint8_t *bits_out)
+{
+    if (int st = alloc_args_status(n_tags, N, D2, D4, B, bits_out)) return st;
+    if (n_tags == 0) return TKV_OK;
+    std::vector<double> rho((size_t)n_tags);
+    for (int32_t k = 0; k < n_tags; ++k) {
+        const double gain = D2[k] - D4[k];
+        if (N[k] == 0) rho[(size_t)k] = gain > 0 ? INFINITY : (gain < 0 ? -INFINITY : 0.0);
+        else rho[(size_t)k] = gain / (2.0 * (double)N[k]);
+    }
+    std::vector<int32_t> order((size_t)n_tags);
+    for (int32_t k = 0; k < n_tags; ++k) order[(size_t)k] = k;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return rho[(size_t)a] > rho[(size_t)b]; });
+    int64_t sum = 0;
+    const double limit = alloc_limit(n_tags, N, B, &sum);
+    int64_t used = 2 * sum;
+    for (int32_t k = 0; k < n_tags; ++k) bits_out[k] = 2;
+    for (int32_t k : order)
+        if ((double)(used + 2 * N[k]) <= limit) {
+            bits_out[k] = 4;
+            used += 2 * N[k];
+        }
+    return TKV_OK;
+}
+
+int tkv_allocate_bits_exhaustive(int32_t n_tags, const int64_t *N, const double *D2, const double *D4,
+                                 double B, uint8_t *bits_out)
+{
+    if (n_tags > 22) return TKV_ERR_INVALID_ARG;
+    if (int st = alloc_args_status(n_tags, N, D2, D4, B, bits_out)) return st;
+    if (n_tags == 0) return TKV_OK;
+    int64_t sum = 0;
+    const double limit = alloc_limit(n_tags, N, B, &sum);
+    bool have = false;
+    double best_cost = 0.0;
+    int64_t best_used = 0;
+    uint32_t best_mask = 0;
+    for (uint32_t mask = 0; mask < (1u << n_tags); ++mask) {
+        int64_t used = 2 * sum;
+        for (int32_t k = 0; k < n_tags; ++k)
+            if ((mask >> k) & 1u) used += 2 * N[k];
+        if ((double)used > limit) continue;
+        double cost = 0.0;   // summed in tag order
+        for (int32_t k = 0; k < n_tags; ++k) cost = cost + (((mask >> k) & 1u) ? D4[k] : D2[k]);
+        if (!have || cost < best_cost || (cost == best_cost && used < best_used)) {
+            have = true;
+            best_cost = cost;
+            best_used = used;
+            best_mask = mask;
+        }
+    }
+    for (int32_t k = 0; k < n_tags; ++k) bits_out[k] = ((best_mask >> k) & 1u) ? 4 : 2;
+    return TKV_OK;
 }
 
 int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,

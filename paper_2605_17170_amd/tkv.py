@@ -37,7 +37,7 @@ EXPORTS = [
     "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
     "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
-    "tkv_decode_split", "tkv_decode_reduce",
+    "tkv_decode_split", "tkv_decode_reduce", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
 ]
 
 
@@ -112,6 +112,10 @@ def lib():
                                            vp, vp, sz, vp, vp]
         L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
         L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
+        for fn in (L.tkv_allocate_bits_greedy, L.tkv_allocate_bits_exhaustive):
+            fn.restype = C.c_int
+            fn.argtypes = [i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
+                           C.POINTER(C.c_uint8)]
         _lib = L
     return _lib
 
@@ -345,3 +349,23 @@ def tkv_decode_reduce(desc, seq_item_indptr, n_items: int, out, workspace, strea
     assert seq_item_indptr.numel() == batch + 1 and out.element_size() == 4
     _check(lib().tkv_decode_reduce(C.byref(desc), _dev(seq_item_indptr), n_items, batch, n_q_heads, _dev(out),
                                    _dev(workspace), ws_bytes, _stream(stream)), "tkv_decode_reduce")
+
+
+def _allocate_bits(fn, name, N, D2, D4, B):
+    n = len(N)
+    if not (len(D2) == n and len(D4) == n):
+        raise ValueError("N, D2 and D4 must have one entry per tag")
+    out = (C.c_uint8 * n)()
+    _check(fn(n, (C.c_int64 * n)(*[int(x) for x in N]), (C.c_double * n)(*[float(x) for x in D2]),
+              (C.c_double * n)(*[float(x) for x in D4]), float(B), out), name)
+    return list(out)
+
+
+def tkv_allocate_bits_greedy(N, D2, D4, B):
+    """Tag bitwidths (2 or 4) by the greedy walk over per-bit gains; argument marshalling only."""
+    return _allocate_bits(lib().tkv_allocate_bits_greedy, "tkv_allocate_bits_greedy", N, D2, D4, B)
+
+
+def tkv_allocate_bits_exhaustive(N, D2, D4, B):
+    """Tag bitwidths (2 or 4) by exhaustive search, at most 22 tags; argument marshalling only."""
+    return _allocate_bits(lib().tkv_allocate_bits_exhaustive, "tkv_allocate_bits_exhaustive", N, D2, D4, B)

@@ -102,3 +102,46 @@ def test_oracle_greedy_is_optimal_for_equal_counts_and_positive_gains():
         g = A.allocate_greedy(N, D2, D4, B)
         e = A.allocate_exhaustive(N, D2, D4, B)
         assert abs(A.total_distortion(g, D2, D4) - A.total_distortion(e, D2, D4)) < 1e-12
+# ------------------------------------------------------------------ library against the oracle
+def _lib_alloc(fn, N, D2, D4, B):
+    n = len(N)
+    Na = (C.c_int64 * n)(*N)
+    a2 = (C.c_double * n)(*D2)
+    a4 = (C.c_double * n)(*D4)
+    out = (C.c_uint8 * n)()
+    rc = fn(n, Na, a2, a4, C.c_double(B), out)
+    return rc, list(out)
+
+
+def test_library_matches_oracle():
+    L = tkv.lib()
+    rng = np.random.default_rng(73)
+    for i in range(300):
+        n = int(rng.integers(1, 13))
+        N, D2, D4, B = _random_instance(rng, n)
+        if i % 7 == 0:                      # ties in rho and in the optimum
+            D2 = [round(x, 1) for x in D2]
+            D4 = [round(x, 1) for x in D4]
+            N = [max(1, x // 10 * 10) for x in N]
+        rc, bits = _lib_alloc(L.tkv_allocate_bits_greedy, N, D2, D4, B)
+        assert rc == tkv.TKV_OK and bits == A.allocate_greedy(N, D2, D4, B)
+        rc, bits = _lib_alloc(L.tkv_allocate_bits_exhaustive, N, D2, D4, B)
+        assert rc == tkv.TKV_OK and bits == A.allocate_exhaustive(N, D2, D4, B)
+    g = _gold()
+    N = [int(x) for x in g["N"]]
+    assert _lib_alloc(L.tkv_allocate_bits_greedy, N, g["D2"], g["D4"], g["B"][0])[1] == [int(x) for x in g["greedy"]]
+    N2 = [int(x) for x in g["N2"]]
+    assert _lib_alloc(L.tkv_allocate_bits_exhaustive, N2, g["D2_2"], g["D4_2"], g["B2"][0])[1] == [int(x) for x in g["exhaustive2"]]
+
+
+def test_library_large_greedy_and_errors():
+    L = tkv.lib()
+    rng = np.random.default_rng(74)
+    N, D2, D4, B = _random_instance(rng, 56)            # the paper's 56-tag space
+    rc, bits = _lib_alloc(L.tkv_allocate_bits_greedy, N, D2, D4, B)
+    assert rc == tkv.TKV_OK and bits == A.allocate_greedy(N, D2, D4, B)
+    assert _lib_alloc(L.tkv_allocate_bits_exhaustive, N, D2, D4, B)[0] == tkv.TKV_ERR_INVALID_ARG   # > 22 tags
+    assert _lib_alloc(L.tkv_allocate_bits_greedy, [1, 2], [1.0, 1.0], [0.5, 0.5], 1.5)[0] == tkv.TKV_ERR_INVALID_ARG
+    assert _lib_alloc(L.tkv_allocate_bits_greedy, [1, -2], [1.0, 1.0], [0.5, 0.5], 3.0)[0] == tkv.TKV_ERR_INVALID_ARG
+    assert _lib_alloc(L.tkv_allocate_bits_greedy, [1, 2], [1.0, float("nan")], [0.5, 0.5], 3.0)[0] == tkv.TKV_ERR_INVALID_ARG
+    assert L.tkv_allocate_bits_greedy(0, None, None, None, C.c_double(3.0), None) == tkv.TKV_OK
