@@ -11,6 +11,10 @@
  *     (scale, zero-point) pair per group of channels of one token and head
  *     (Sec. 3.2.1, "Bitwidths and quantization axes"; the per-token axis is
  *     used for keys and values at both widths);
+ *   - the paper's own scheme for INT2 keys (Sec. 3.2.1): per-channel groups, the
+ *     32 tokens of a block sharing one (scale, zero-point) pair per channel; the
+ *     residual policy (tokens that do not fill a block go to INT4) is the few
+ *     lines of route_residual in tkv_oracle.py;
  *   - sub-byte packing of the codes plus scales and zero-points into paged
  *     UINT8 buffers, one pool per bitwidth in a shared index space split by
  *     an offset (Sec. 3.2.1 "Buffer layout", Sec. 3.2.2 "Shared address
@@ -35,7 +39,10 @@
  * round-trip bound, exactly-representable inputs against unquantised fp64
  * attention, brute force on tiny heads, closed forms, codec bijectivity and
  * hand-derived bit positions; the FP16 dequantisation against numpy's
- * float64 -> float16 cast and exact rational arithmetic.  No function here
+ * float64 -> float16 cast and exact rational arithmetic; the per-channel keys
+ * against a hand-worked block, numpy reductions over the token axis, exact
+ * nearest-code search and the per-token path on the transposed block
+ * (tests/test_oracle_kchannel.py).  No function here
  * is "parity unpinned".
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
@@ -191,6 +198,32 @@ int tkvo_quantize(const uint16_t *x, int64_t T, int H, int D, int G, const uint8
                 int64_t e = (t * H + h) * (int64_t)D + (int64_t)g * G;
                 int64_t m = (t * H + h) * (int64_t)NG + g;
                 tkvo_quantize_group(x + e, G, bits[t], codes + e, scale + m, zero + m);
+            }
+    return 0;
+}
+
+/* Per-channel key quantisation (Sec. 3.2.1, quantisation axes of the INT2 keys): the G tokens of a
+ * block share one (scale, zero-point) pair FOR EACH CHANNEL, i.e. the quantisation group is the column of G
+ * token values of one channel and head; the arithmetic of a group is the one above.
+ * x: bf16 [T, H, D]; tok: i64 [nb, G], the token rows of each block in slot order.
+ * codes: u8 [T, H, D], only the rows named by tok are written; bscale, bzero: fp16 bit patterns [nb, H, D].
+ * Returns 0, -1 on a bad argument (bitwidth, G > 64, a row outside [0, T)). */
+int tkvo_quantize_k_channel(const uint16_t *x, int64_t T, int H, int D, int G, int bits,
+                            const int64_t *tok, int64_t nb,
+                            uint8_t *codes, uint16_t *bscale, uint16_t *bzero)
+{
+    if ((bits != 2 && bits != 4) || G <= 0 || G > 64) return -1;
+    for (int64_t i = 0; i < nb * G; ++i) if (tok[i] < 0 || tok[i] >= T) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < nb; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int c = 0; c < D; ++c) {
+                uint16_t col[64];
+                uint8_t cc[64];
+                for (int i = 0; i < G; ++i) col[i] = x[(tok[b * G + i] * H + h) * (int64_t)D + c];
+                int64_t m = (b * H + h) * (int64_t)D + c;
+                tkvo_quantize_group(col, G, bits, cc, bscale + m, bzero + m);
+                for (int i = 0; i < G; ++i) codes[(tok[b * G + i] * H + h) * (int64_t)D + c] = cc[i];
             }
     return 0;
 }
@@ -389,6 +422,17 @@ void tkvo_vcode_pos(int bits, int t, int c, int *word, int *shift)
 
 /* K scale / K zero: fp16 [token][group]. */
 int tkvo_kmeta_index(int t, int g) { return t * 4 + g; }
+/* K scale / K zero of a page whose INT2 keys are quantised per channel: fp16 [block t/32][position of the
+ * channel], 128 positions per block.  The position lists the channels in the order the decode kernel's
+ * matrix operand holds them: chunks of 8 values per (group c/32, quarter), quarter = 2*((c%32)/16) + (c%8)/4,
+ * and inside a chunk the pair (c, c+8) of k = c%4 sits at 2k, 2k+1. */
+int tkvo_kcmeta_index(int blk, int c)
+{
+    int g = c / 32, r = c % 32;
+    int quarter = 2 * (r / 16) + (r % 8) / 4;
+    int k = r % 4, hi = (r % 16) / 8;
+    return ((blk * 4 + g) * 4 + quarter) * 8 + 2 * k + hi;
+}
 /* V scale / V zero: fp16 in chunks of 8 tokens [block t/32][quad][group][j]
  * with j as above (the order in which a word of V codes lists its tokens). */
 int tkvo_vmeta_index(int t, int g)
@@ -445,6 +489,22 @@ void tkvo_record_get_token(const uint8_t *rec, int bits, int t,
         kz[g] = get_h(rec + off_kz(bits), tkvo_kmeta_index(t, g));
         vs[g] = get_h(rec + off_vs(bits), tkvo_vmeta_index(t, g));
         vz[g] = get_h(rec + off_vz(bits), tkvo_vmeta_index(t, g));
+    }
+}
+
+/* Per-channel key metadata of one 32-token block of an INT2 record: scale, zero fp16 [128]. */
+void tkvo_record_put_kblock(uint8_t *rec, int blk, const uint16_t *ks, const uint16_t *kz)
+{
+    for (int c = 0; c < HD; ++c) {
+        put_h(rec + off_ks(2), tkvo_kcmeta_index(blk, c), ks[c]);
+        put_h(rec + off_kz(2), tkvo_kcmeta_index(blk, c), kz[c]);
+    }
+}
+void tkvo_record_get_kblock(const uint8_t *rec, int blk, uint16_t *ks, uint16_t *kz)
+{
+    for (int c = 0; c < HD; ++c) {
+        ks[c] = get_h(rec + off_ks(2), tkvo_kcmeta_index(blk, c));
+        kz[c] = get_h(rec + off_kz(2), tkvo_kcmeta_index(blk, c));
     }
 }
 

@@ -134,6 +134,94 @@ def dequantize(codes, scale, zero, G: int = GS):
     return out
 
 
+# ------------------------------------------------- per-channel INT2 keys (Sec. 3.2.1)
+def route_residual(bits_u8, G: int = GS):
+    """Residual policy for INT2 keys (Sec. 3.2.1): per-channel quantisation needs whole groups of G tokens,
+    so the INT2-tagged tokens of one arriving sequence chunk that do not fill a group -- the last
+    (count mod G) of them -- take the INT4 per-token path.  Returns the rewritten per-token bitwidth array."""
+    bits = np.array(bits_u8, np.uint8, copy=True)
+    idx = np.flatnonzero(bits == 2)
+    r = idx.size % G
+    if r:
+        bits[idx[idx.size - r:]] = 4
+    return bits
+
+
+def int2_blocks(bits_u8, base: int = 0, G: int = GS):
+    """Token rows of the groups of G INT2 tokens, in arrival order: i64 [nb, G] (rows offset by `base`)."""
+    idx = np.flatnonzero(np.asarray(bits_u8) == 2)
+    assert idx.size % G == 0, "route_residual first"
+    return (idx.reshape(-1, G) + base).astype(np.int64)
+
+
+def quantize_k_channel(x_u16, tok_blocks, codes_out, bits: int = 2):
+    """Keys quantised per channel over blocks of G tokens.  x: bf16 bits [T,H,D]; tok_blocks i64 [nb,G];
+    codes_out u8 [T,H,D] receives the codes of the listed rows.  Returns (bscale, bzero) u16 [nb,H,D]."""
+    x = _c(x_u16, np.uint16)
+    tok = _c(tok_blocks, np.int64)
+    T, H, D = x.shape
+    nb, G = tok.shape if tok.ndim == 2 else (0, GS)
+    assert codes_out.dtype == np.uint8 and codes_out.flags.c_contiguous and codes_out.shape == x.shape
+    bs = np.empty((nb, H, D), np.uint16)
+    bz = np.empty((nb, H, D), np.uint16)
+    rc = lib().tkvo_quantize_k_channel(_p(x), C.c_int64(T), C.c_int(H), C.c_int(D), C.c_int(G), C.c_int(bits),
+                                       _p(tok), C.c_int64(nb), _p(codes_out), _p(bs), _p(bz))
+    if rc:
+        raise ValueError("oracle quantize_k_channel: bad argument")
+    return bs, bz
+
+
+def dequantize_k_channel(codes, tok_blocks, bscale, bzero, out_f64):
+    """x_hat = code * scale + zero (exact in fp64) written into the listed rows of out_f64 [T,H,D]."""
+    tok = np.asarray(tok_blocks, np.int64)
+    if tok.size == 0:
+        return out_f64
+    s = f16_to_f32(bscale).astype(np.float64)[:, None]     # [nb,1,H,D]
+    z = f16_to_f32(bzero).astype(np.float64)[:, None]
+    out_f64[tok] = codes[tok].astype(np.float64) * s + z   # rows [nb,G,H,D]
+    return out_f64
+
+
+def kcmeta_index(blk, c):
+    return int(lib().tkvo_kcmeta_index(C.c_int(blk), C.c_int(c)))
+
+
+def put_kblocks(pool_u8, Hkv, P2, slot_ids, tok_blocks, bscale, bzero):
+    """Write the per-channel key metadata of every block into the record of the page its tokens sit in."""
+    assert pool_u8.dtype == np.uint8 and pool_u8.flags.c_contiguous
+    tok = np.asarray(tok_blocks, np.int64)
+    bs, bz = _c(bscale, np.uint16), _c(bzero, np.uint16)
+    for b in range(tok.shape[0]):
+        sl = np.asarray(slot_ids)[tok[b]]
+        page, slot0 = int(sl[0]) // TP, int(sl[0]) % TP
+        assert slot0 % GS == 0 and np.array_equal(sl, sl[0] + np.arange(GS)) and page < P2
+        for h in range(Hkv):
+            off, _ = record_offset(Hkv, P2, page, h)
+            rec = pool_u8[off:off + record_bytes(2)]
+            lib().tkvo_record_put_kblock(_p(rec), C.c_int(slot0 // GS), _p(np.ascontiguousarray(bs[b, h])),
+                                         _p(np.ascontiguousarray(bz[b, h])))
+
+
+def get_kblocks(pool_u8, Hkv, P2, slot_ids, tok_blocks):
+    """Read back (bscale, bzero) u16 [nb,H,D] of the listed blocks from a pool."""
+    pool = _c(pool_u8, np.uint8)
+    tok = np.asarray(tok_blocks, np.int64)
+    nb = tok.shape[0]
+    bs = np.empty((nb, Hkv, HD), np.uint16)
+    bz = np.empty((nb, Hkv, HD), np.uint16)
+    for b in range(nb):
+        s0 = int(np.asarray(slot_ids)[tok[b, 0]])
+        page, blk = s0 // TP, (s0 % TP) // GS
+        for h in range(Hkv):
+            off, _ = record_offset(Hkv, P2, page, h)
+            rec = pool[off:off + record_bytes(2)]
+            ks = np.empty(HD, np.uint16)
+            kz = np.empty(HD, np.uint16)
+            lib().tkvo_record_get_kblock(_p(rec), C.c_int(blk), _p(ks), _p(kz))
+            bs[b, h], bz[b, h] = ks, kz
+    return bs, bz
+
+
 # ---------------------------------------------------------------- attention
 def dequantize_f16(codes, scale, zero, G: int = GS):
     """The cached rows as FP16 bit patterns [T,H,D] (Sec. 3.2.3 "Prefill"): nearest-even of the exact
