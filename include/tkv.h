@@ -48,7 +48,8 @@ enum {
     TKV_STATUS_TAG_MISMATCH = 1,     /* append: tag_bits[token] differs from its page's pool width (token skipped) */
     TKV_STATUS_BITMAP_MISMATCH = 2,  /* decode: bit_map[page] differs from the width its position implies (page skipped) */
     TKV_STATUS_PAGE_RANGE = 4,       /* a page id read on the device lies outside the pool (page skipped) */
-    TKV_STATUS_DST_RANGE = 8         /* tkv_gather_dequant: an output row index >= n_tokens (slot skipped) */
+    TKV_STATUS_DST_RANGE = 8,        /* tkv_gather_dequant: an output row index >= n_tokens (slot skipped) */
+    TKV_STATUS_BLOCK_PARTIAL = 16    /* append, per-channel INT2 keys: a 32-token block arrived incomplete (block skipped) */
 };
 
 const char *tkv_strerror(int status);
@@ -66,7 +67,23 @@ typedef struct tkv_desc {
     int32_t page_tokens;    /* 64  */
     int32_t n_pages_int2;
     int32_t n_pages_int4;
+    int32_t int2_key_axis;  /* TKV_KEYS_PER_TOKEN or TKV_KEYS_PER_CHANNEL */
 } tkv_desc;
+
+/*
+ * Quantisation axis of the keys in the INT2 pool (Sec. 3.2.1, "Bitwidths and
+ * quantization axes").  Values and INT4 keys are always per token: a group is
+ * 32 consecutive channels of one token.
+ *   TKV_KEYS_PER_TOKEN    INT2 keys are grouped the same way.
+ *   TKV_KEYS_PER_CHANNEL  the paper's scheme: the 32 tokens of a block (slots
+ *       0..31 or 32..63 of an INT2 page) share one (scale, zero-point) pair
+ *       per channel.  A block is quantised in one piece, so INT2 tokens arrive
+ *       in whole blocks: the stream of a sequence's INT2 tokens always holds a
+ *       multiple of 32 tokens, and tokens that do not fill a block are stored
+ *       at INT4 (tkv_route_residual).  The record size is the same; the K
+ *       scale / K zero planes hold fp16 [block][128 channel positions].
+ */
+enum { TKV_KEYS_PER_TOKEN = 0, TKV_KEYS_PER_CHANNEL = 1 };
 
 /* Bytes of one (page, kv head) record: 6144 for bits = 2, 10240 for bits = 4, 0 otherwise
  * (codes of K and V plus fp16 scale and zero-point per group of 32 channels, Sec. 3.2.1). */
@@ -146,6 +163,16 @@ int tkv_allocate_bits_exhaustive(int32_t n_tags, const int64_t *N, const double 
 /* ------------------------------------------------------------------ */
 /* Q1: route newly arrived tokens to slots (host).                      */
 /* ------------------------------------------------------------------ */
+/*
+ * Residual policy of the per-channel INT2 keys (Sec. 3.2.1): of the tokens
+ * tagged INT2 in tag_bits (host, u8[n_tokens], one arriving chunk of one
+ * sequence) the last (count mod 32) do not fill a block and are stored at
+ * INT4.  bits_out (host, u8[n_tokens], may alias tag_bits) receives the
+ * per-token widths to hand to tkv_plan_append and tkv_quantize_append.
+ * Errors: TKV_ERR_INVALID_ARG, TKV_ERR_BAD_BITS.
+ */
+int tkv_route_residual(const uint8_t *tag_bits, int32_t n_tokens, uint8_t *bits_out);
+
 /* Upper bound of pages one tkv_plan_append call over n_tokens can touch. */
 int32_t tkv_plan_append_max_work(int32_t n_tokens);
 /*
@@ -160,7 +187,9 @@ int32_t tkv_plan_append_max_work(int32_t n_tokens);
  *                               index of the token that goes there, or -1;
  *   *n_work_out                 number of pages listed.
  * token_base lets several sequences' plans address one concatenated K/V
- * tensor.  On any error the sequence and the allocator are left unchanged.
+ * tensor.  With TKV_KEYS_PER_CHANNEL the number of INT2 tokens must be a
+ * multiple of 32 (TKV_ERR_INVALID_ARG otherwise; see tkv_route_residual).
+ * On any error the sequence and the allocator are left unchanged.
  */
 int tkv_plan_append(tkv_alloc *a, tkv_seq *s, const uint8_t *tag_bits, int32_t n_tokens,
                     int32_t token_base, int32_t *slot_ids_out, int32_t *work_pages_out,
@@ -173,9 +202,13 @@ int tkv_plan_append(tkv_alloc *a, tkv_seq *s, const uint8_t *tag_bits, int32_t n
  * For every listed page and kv head: asymmetric min/max quantisation of each
  * group of 32 channels of each arriving token (zero = fp16(min), scale =
  * fp16((max-min)/(2^b-1)), code = round-half-even((x-zero)*(1/scale)) clamped),
- * per-token for K and V at both widths (Sec. 3.2.1), packed into the page's
- * planes; bit_map[page] is set to the page's width.  Bits of slots whose
- * work_src entry is -1 are left untouched.
+ * per-token for K and V at both widths, or, with TKV_KEYS_PER_CHANNEL, the
+ * keys of INT2 pages per channel over each block of 32 slots (Sec. 3.2.1),
+ * packed into the page's planes; bit_map[page] is set to the page's width.
+ * Bits of slots whose work_src entry is -1 are left untouched.  With
+ * TKV_KEYS_PER_CHANNEL the 32 slots of a block of an INT2 page must all be
+ * named or all be -1; a block named in part is skipped (keys and values) and
+ * TKV_STATUS_BLOCK_PARTIAL is raised.
  *   pool       device, tkv_pool_bytes(desc) bytes, 256-byte aligned
  *   bit_map    device u8[n_pages_int2 + n_pages_int4]
  *   K, V       device bf16 [n_tokens, n_kv_heads, head_dim], contiguous

@@ -18,6 +18,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "tkv_internal.h"
 #include "tkv_layout.h"
 
@@ -33,21 +35,12 @@ struct GroupQ {
     uint16_t scale, zero;
 };
 
+// One quantisation group of 32 values: the channels of a group of one token, or (per-channel keys) the 32
+// tokens of a block for one channel.
 template <int BITS>
-__device__ __forceinline__ GroupQ quantize_group(const uint4 *src)
+__device__ __forceinline__ GroupQ quantize_values(const float (&f)[32])
 {
     constexpr int L = (1 << BITS) - 1;
-    float f[32];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint4 v = src[i];
-        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            f[8 * i + 2 * k] = __uint_as_float(u[k] << 16);
-            f[8 * i + 2 * k + 1] = __uint_as_float(u[k] & 0xffff0000u);
-        }
-    }
     float mn = f[0], mx = f[0];
 #pragma unroll
     for (int i = 1; i < 32; ++i) {
@@ -82,9 +75,35 @@ __device__ __forceinline__ GroupQ quantize_group(const uint4 *src)
 }
 
 template <int BITS>
+__device__ __forceinline__ GroupQ quantize_group(const uint4 *src)
+{
+    float f[32];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 v = src[i];
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[8 * i + 2 * k] = __uint_as_float(u[k] << 16);
+            f[8 * i + 2 * k + 1] = __uint_as_float(u[k] & 0xffff0000u);
+        }
+    }
+    return quantize_values<BITS>(f);
+}
+
+// LDS of the per-channel key path: the bf16 keys of the page [slot][channel], then their codes one per byte.
+struct KcLds {
+    alignas(16) uint16_t kt[kPageTokens][kHeadDim];
+    alignas(16) uint8_t kcodes[kPageTokens][kHeadDim];
+    int n_in_block[2];
+};
+struct NoLds {};
+
+// KC: keys per channel over each block of 32 slots (INT2 pages only); `valid` is then uniform over a block.
+template <int BITS, bool KC, class KL>
 __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, const uint16_t *V, int src,
                                               bool valid, int head, int n_kv_heads,
-                                              uint32_t (*lds_codes)[32], uint8_t *lds_valid)
+                                              uint32_t (*lds_codes)[32], uint8_t *lds_valid, KL &kl)
 {
     using R = Rec<BITS>;
     const int tid = threadIdx.x, slot = tid >> 2, g = tid & 3;
@@ -92,13 +111,21 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
     if (g == 0) lds_valid[slot] = valid;
     if (valid) {
         const size_t e = ((size_t)src * n_kv_heads + head) * kHeadDim + g * kGroup;
-        const GroupQ kq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(K + e));
-        uint32_t *kc = reinterpret_cast<uint32_t *>(rec + R::kKCodes);
-        constexpr int words = BITS;   // 32-bit words of codes per group: 4 (INT4) or 2 (INT2)
+        if constexpr (KC) {
+            // the keys wait in LDS until the whole block is there
+            const uint4 *ksrc = reinterpret_cast<const uint4 *>(K + e);
+            uint4 *kdst = reinterpret_cast<uint4 *>(&kl.kt[slot][g * kGroup]);
 #pragma unroll
-        for (int w = 0; w < words; ++w) kc[((tile * words + w) * 16 + row) * 4 + g] = kq.words[w];
-        reinterpret_cast<uint16_t *>(rec + R::kKScale)[slot * 4 + g] = kq.scale;
-        reinterpret_cast<uint16_t *>(rec + R::kKZero)[slot * 4 + g] = kq.zero;
+            for (int i = 0; i < 4; ++i) kdst[i] = ksrc[i];
+        } else {
+            const GroupQ kq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(K + e));
+            uint32_t *kc = reinterpret_cast<uint32_t *>(rec + R::kKCodes);
+            constexpr int words = BITS;   // 32-bit words of codes per group: 4 (INT4) or 2 (INT2)
+#pragma unroll
+            for (int w = 0; w < words; ++w) kc[((tile * words + w) * 16 + row) * 4 + g] = kq.words[w];
+            reinterpret_cast<uint16_t *>(rec + R::kKScale)[slot * 4 + g] = kq.scale;
+            reinterpret_cast<uint16_t *>(rec + R::kKZero)[slot * 4 + g] = kq.zero;
+        }
 
         const GroupQ vq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(V + e));
         const int mi = vmeta_index(slot, g);
@@ -109,6 +136,46 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
         dst[1] = make_uint4(vq.bytes[4], vq.bytes[5], vq.bytes[6], vq.bytes[7]);
     }
     __syncthreads();
+    if constexpr (KC) {
+        // thread (block, channel): the block's 32 token values of one channel are one quantisation group
+        {
+            const int blk = tid >> 7, c = tid & 127;
+            if (kl.n_in_block[blk] == kGroup) {
+                float f[32];
+#pragma unroll
+                for (int i = 0; i < 32; ++i) f[i] = __uint_as_float((uint32_t)kl.kt[32 * blk + i][c] << 16);
+                const GroupQ kq = quantize_values<BITS>(f);
+                const int mi = kcmeta_index(blk, c);
+                reinterpret_cast<uint16_t *>(rec + R::kKScale)[mi] = kq.scale;
+                reinterpret_cast<uint16_t *>(rec + R::kKZero)[mi] = kq.zero;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) kl.kcodes[32 * blk + i][c] = (uint8_t)(kq.bytes[i >> 2] >> (8 * (i & 3)));
+            }
+        }
+        __syncthreads();
+        // thread (slot, group) again: its token's 32 codes of the group, packed as in the per-token layout
+        if (valid) {
+            const uint4 *cb = reinterpret_cast<const uint4 *>(&kl.kcodes[slot][g * kGroup]);
+            uint32_t *kc = reinterpret_cast<uint32_t *>(rec + R::kKCodes);
+            constexpr int words = BITS;
+            constexpr int per_word = 32 / BITS;
+            uint32_t wv[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const uint4 v = cb[q];
+                const uint32_t b4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int i = 16 * q + 4 * j + k;   // channel of the group
+                        wv[i / per_word] |= ((b4[j] >> (8 * k)) & 0xffu) << (BITS * (i % per_word));
+                    }
+            }
+#pragma unroll
+            for (int w = 0; w < words; ++w) kc[((tile * words + w) * 16 + row) * 4 + g] = wv[w];
+        }
+    }
     // V codes: one 32-bit word = one channel x (8 | 16) tokens of one quad
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(lds_codes);
     uint32_t *vc = reinterpret_cast<uint32_t *>(rec + R::kVCodes);
@@ -140,6 +207,7 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
     }
 }
 
+template <bool KC>
 __global__ __launch_bounds__(256) void tkv_append_kernel(
     uint8_t *__restrict__ pool, uint8_t *__restrict__ bit_map, const uint16_t *__restrict__ K,
     const uint16_t *__restrict__ V, const uint8_t *__restrict__ tag_bits, int n_tokens,
@@ -148,6 +216,7 @@ __global__ __launch_bounds__(256) void tkv_append_kernel(
 {
     __shared__ __attribute__((aligned(16))) uint32_t lds_codes[kPageTokens][32];
     __shared__ uint8_t lds_valid[kPageTokens];
+    __shared__ typename std::conditional<KC, KcLds, NoLds>::type kl;
     const int w = blockIdx.x / n_kv_heads, head = blockIdx.x % n_kv_heads;
     const int page = work_pages[w];
     if (page < 0 || page >= n_pages_int2 + n_pages_int4) {
@@ -163,8 +232,26 @@ __global__ __launch_bounds__(256) void tkv_append_kernel(
         if (status && (threadIdx.x & 3) == 0) atomicOr(status, TKV_STATUS_TAG_MISMATCH);
     }
     uint8_t *rec = pool + record_offset(page, head, n_kv_heads, n_pages_int2);
-    if (bits == 2) append_record<2>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid);
-    else append_record<4>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid);
+    if constexpr (KC) {
+        if (bits == 2) {
+            // a block of 32 slots is quantised in one piece: it takes part whole or not at all
+            if (threadIdx.x < 2) kl.n_in_block[threadIdx.x] = 0;
+            __syncthreads();
+            if ((threadIdx.x & 3) == 0 && valid) atomicAdd(&kl.n_in_block[slot >> 5], 1);
+            __syncthreads();
+            const int n = kl.n_in_block[slot >> 5];
+            if (n != 0 && n != kGroup) {
+                valid = false;
+                if (status && (threadIdx.x & 127) == 0) atomicOr(status, TKV_STATUS_BLOCK_PARTIAL);
+            }
+            append_record<2, true>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+        } else {
+            append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+        }
+    } else {
+        if (bits == 2) append_record<2, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+        else append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+    }
     if (head == 0 && __syncthreads_or(valid) && threadIdx.x == 0) bit_map[page] = (uint8_t)bits;
 }
 
@@ -175,7 +262,8 @@ int tkv_launch_append(const tkv_desc *desc, void *pool, uint8_t *bit_map, const 
                       const int32_t *work_src, int32_t n_work, int32_t *status, void *stream)
 {
     const dim3 grid((unsigned)(n_work * desc->n_kv_heads)), block(256);
-    hipLaunchKernelGGL(tkv_append_kernel, grid, block, 0, (hipStream_t)stream, (uint8_t *)pool, bit_map,
+    auto kernel = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL ? tkv_append_kernel<true> : tkv_append_kernel<false>;
+    hipLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)stream, (uint8_t *)pool, bit_map,
                        (const uint16_t *)K, (const uint16_t *)V, tag_bits, n_tokens, work_pages, work_src,
                        desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4, status);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;

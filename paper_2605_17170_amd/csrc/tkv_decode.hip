@@ -36,6 +36,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "tkv_internal.h"
 #include "tkv_layout.h"
 
@@ -60,6 +62,9 @@ constexpr int kPExp = 8;
 constexpr int kVExp = -1;
 // W * staged scale must stay finite in fp16: the staged scale is clamped to 65504 / 2^(kTau + kPExp)
 constexpr uint32_t kVsClamp = 0x4bff4bffu;   // fp16 15.99 twice
+// Per-channel INT2 keys: q'' (q normalised, times its slot factor) stays below 2^6 and is multiplied by the K scale in fp16; the scale saturates at 1023.
+constexpr uint32_t kKcClamp = 0x63fe63feu;   // fp16 1023 twice
+constexpr int kKcQExp = 9;   // the first slot factor is 2^-3, so q'' stays below 2^6
 
 __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
@@ -113,6 +118,11 @@ __device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
+// The value of the lane eight columns on in the same row of 16 lanes.
+__device__ __forceinline__ float row_ror8(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+}
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll
@@ -135,7 +145,15 @@ struct WaveState {
 };
 
 
-struct alignas(16) Lds {
+// Only the kernel for per-channel INT2 keys holds the second q operand.
+template <bool KC> struct LdsExtra {};
+template <> struct LdsExtra<true> {
+    alignas(16) uint4 qp[kGroups][64];                   // q * 2^E in the slot order of qo, without the slot factors
+};
+template <bool KC> struct alignas(16) Lds : LdsExtra<KC> {
+    // Per-channel INT2 keys reuse ks and kz while INT2 pages run: ks holds the K scale plane (512 B) and the
+    // K zero plane (512 B) of the page as stored, kz a plane of zeros (the INT4 pages, which come later in
+    // an item, overwrite all three with their own staging).
     alignas(16) float ks[kPageTokens * kGroups];         // K scale * F, fp32 [token][group]
     alignas(16) uint32_t vs[kPageTokens * kGroups / 2];  // V scale * 2^(kVExp - pos), fp16 pairs in plane order
     alignas(16) uint32_t vz[kPageTokens * kGroups / 2];  // V zero, fp16 pairs in plane order
@@ -143,17 +161,21 @@ struct alignas(16) Lds {
     alignas(16) uint4 qo[kGroups][64];                   // B operand of the QK^T MFMAs per group and lane
     alignas(16) float alpha[16];
     alignas(16) float zl[8][8];
+    __device__ __forceinline__ uint4 *kc_scale() { return reinterpret_cast<uint4 *>(ks); }
+    __device__ __forceinline__ uint4 *kc_zero() { return reinterpret_cast<uint4 *>(ks) + 32; }
+    __device__ __forceinline__ uint4 *kc_nil() { return reinterpret_cast<uint4 *>(kz); }
 };
 
 // B operand of the QK^T MFMAs for one width, kept in LDS: per group and lane, 4 registers of fp16
 // pairs holding q' = q * 2^E * 2^-pos in the slot order the unpack produces.
-template <int BITS>
-__device__ __forceinline__ void build_q_operand(const float *qf /* this lane's head, 128 floats (q * 2^E) in LDS */, int q4,
-                                               int lane, Lds &lds)
+template <int BITS, bool KC, class QF>
+__device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head, 128 values q * 2^E in LDS */, int q4,
+                                               int lane, Lds<KC> &lds)
 {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        uint32_t r[4];
+        uint32_t r[4], rp[4] = {0, 0, 0, 0};
+        (void)rp;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             int c0, c1;
@@ -168,11 +190,14 @@ __device__ __forceinline__ void build_q_operand(const float *qf /* this lane's h
                 // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 4^k of the 16-channel word q4/2
                 c0 = 32 * g + 16 * (q4 >> 1) + 4 * (q4 & 1) + k;
                 c1 = c0 + 8;
-                f = 1.0f / (float)(1 << (2 * k));
+                // per-channel keys: the unpack leaves the fields three bits higher (see compute_page)
+                f = 1.0f / (float)(1 << (2 * k + (KC ? 3 : 0)));
             }
-            r[k] = pack_h2(qf[c0] * f, qf[c1] * f);
+            r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
+            if constexpr (KC && BITS == 2) rp[k] = pack_h2((float)qf[c0], (float)qf[c1]);
         }
         lds.qo[g][lane] = make_uint4(r[0], r[1], r[2], r[3]);
+        if constexpr (KC && BITS == 2) lds.qp[g][lane] = make_uint4(rp[0], rp[1], rp[2], rp[3]);
     }
 }
 
@@ -219,15 +244,17 @@ struct LaneConst {
     uint32_t vmul01, vmul23;   // fp16 pairs of the staging factor of the V scale
     float negk;           // 0 in head columns 0..7 (hi piece of P), -1 in columns 8..15 (lo piece)
     uint32_t lomask;      // 0 / all ones likewise
+    float zmul;           // per-channel INT2 keys: 2^-24 in head columns 0..7, 0 in columns 8..15
 };
 
 // One page.  `after_qk` runs once the K codes, K zeros and metadata registers of `pr` are dead, `after_pv`
 // once the V codes are: the caller reloads them there for the next page.
-template <int BITS, class AfterQK, class AfterPV>
+template <int BITS, bool KC, class AfterQK, class AfterPV>
 __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_valid, int lane,
-                                             half8 qz, const LaneConst &lc, WaveState &st, Lds &lds,
+                                             half8 qz, const LaneConst &lc, WaveState &st, Lds<KC> &lds,
                                              AfterQK after_qk, AfterPV after_pv)
 {
+    constexpr bool kPerChannel = KC && BITS == 2;   // INT2 keys quantised per channel over 32-token blocks
     const int r16 = lane & 15, q4 = lane >> 4;
     const bool partial = n_valid < kPageTokens;   // wave-uniform: only the last page of a width can be partly filled
 
@@ -245,18 +272,69 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             const uint32_t m23 = (t0 + 2 < n_valid ? 0xffffu : 0u) | (t0 + 3 < n_valid ? 0xffff0000u : 0u);
             vsc.x &= m01; vsc.y &= m23; vzc.x &= m01; vzc.y &= m23;
         }
-        const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
-        reinterpret_cast<float4 *>(lds.ks)[lane] =
-            make_float4((float)a[0] * lc.F, (float)a[1] * lc.F, (float)b[0] * lc.F, (float)b[1] * lc.F);
+        if constexpr (kPerChannel) {
+            // the two key metadata planes as stored: fp16 [block][128 channel positions]
+            reinterpret_cast<uint2 *>(lds.kc_scale())[lane] = make_uint2(pk_min(pr.ksc.x, kKcClamp), pk_min(pr.ksc.y, kKcClamp));
+            reinterpret_cast<uint2 *>(lds.kc_zero())[lane] = pr.kzc;
+        } else {
+            const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
+            reinterpret_cast<float4 *>(lds.ks)[lane] =
+                make_float4((float)a[0] * lc.F, (float)a[1] * lc.F, (float)b[0] * lc.F, (float)b[1] * lc.F);
+            lds.kz[lane] = pr.kzc;
+        }
         reinterpret_cast<uint2 *>(lds.vs)[lane] =
             make_uint2(pk_min(pk_mul(vsc.x, lc.vmul01), kVsClamp), pk_min(pk_mul(vsc.y, lc.vmul23), kVsClamp));
         reinterpret_cast<uint2 *>(lds.vz)[lane] = vzc;
-        lds.kz[lane] = pr.kzc;
     }
     lds_order();
 
     // ---- QK^T: S[e][i] = q . k_hat (unscaled) for token 16e + 4*q4 + i, head column r16
     floatx4 S[4];
+    if constexpr (kPerChannel) {
+        // score = sum_c (q_c s_c) code + sum_c q_c z_c with s, z of the token's block.  q s is formed per block
+        // in two fp16 pieces, exactly (q has 8 significant bits, s 11): head columns 0..7 take
+        // fp16(q s), columns 8..15 the remainder q s - fp16(q s); the columns of a head are added after the
+        // MFMAs.  Lanes of the hi columns read their "rounded product to subtract" from a plane of zeros.
+        const uint4 *sxp = r16 >= 8 ? lds.kc_scale() : lds.kc_nil();
+        const uint32_t rot = (q4 & 1) ? 5u : 29u;   // this lane's 16 codes of a word are its upper / lower half
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            floatx4 z = {0.f, 0.f, 0.f, 0.f};
+            uint32_t b[4][4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int mi = (blk * 4 + g) * 4 + q4;
+                const uint4 zc = lds.kc_zero()[mi];
+                const uint4 qp = lds.qp[g][lane];
+                z = mfma(as_half8(zc.x, zc.y, zc.z, zc.w), as_half8(qp.x, qp.y, qp.z, qp.w), z);   // every row: sum_c q_c z_c
+                const uint4 sc = lds.kc_scale()[mi], sx = sxp[mi], qo = lds.qo[g][lane];
+                b[g][0] = pk_rem(qo.x, sc.x, pk_mul(qo.x, sx.x));
+                b[g][1] = pk_rem(qo.y, sc.y, pk_mul(qo.y, sx.y));
+                b[g][2] = pk_rem(qo.z, sc.z, pk_mul(qo.z, sx.z));
+                b[g][3] = pk_rem(qo.w, sc.w, pk_mul(qo.w, sx.w));
+            }
+            z *= lc.zmul;   // to the unit of the code products, once per head (hi columns only)
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                const int e = 2 * blk + t2;
+                const uint32_t w[4] = {pr.kw[e].x, pr.kw[e].y, pr.kw[e].z, pr.kw[e].w};
+                floatx4 sacc = z;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    // fields at bits 4:3, 6:5, 8:7, 10:9 of each half: q s spans more binades than q, and
+                    // the matrix core drops product bits that fall below its alignment window
+                    const uint32_t ws = __builtin_amdgcn_alignbit(w[g], w[g], rot);   // w >> 5 or w << 3, stray bits fall outside the masks
+                    const half8 a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
+                    sacc = mfma(a, as_half8(b[g][0], b[g][1], b[g][2], b[g][3]), sacc);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sacc[i] += row_ror8(sacc[i]);
+                asm volatile("" : "+v"(sacc));
+                S[e] = sacc;
+            }
+            __builtin_amdgcn_sched_barrier(0);   // one block's operands at a time (register pressure)
+        }
+    } else
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const uint2 kz = lds.kz[16 * e + r16];
@@ -386,12 +464,12 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 }
 
 // All pages [pb, pe) of one width (indices into the sequence's page list).
-template <int BITS>
+template <int BITS, bool KC>
 __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map,
                                           const int32_t *__restrict__ pages, int pb, int pe, int last_index,
                                           int last_valid, int page_lo, int page_hi, int n_pages_total, int kvh,
                                           int n_kv_heads, int n_pages_int2, int item_end, int item_pages, int lane, half8 qz,
-                                          LaneConst lc, WaveState &st, Lds &lds, int32_t *status)
+                                          LaneConst lc, WaveState &st, Lds<KC> &lds, int32_t *status)
 {
     // A V code enters the MFMA as code * 2^(pos - 24), pos = lowest bit of its field after the unpack shift; the
     // staged scale of the slot carries 2^(kVExp - pos).  This lane stages plane entries 4*lane .. 4*lane+3 =
@@ -456,12 +534,14 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
             nv = 0;
         }
         // a page with no valid token still runs (every token masked by count): no second path through the loop
-        compute_page<BITS>(pr, nv, lane, qz, lc, st, lds, after_qk, after_pv);
+        compute_page<BITS, KC>(pr, nv, lane, qz, lc, st, lds, after_qk, after_pv);
         rec = rec_next;
         nv = nv_next;
     }
 }
 
+// KC: the INT2 keys of the pool are quantised per channel over 32-token blocks (Sec. 3.2.1).
+template <bool KC>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PER_EU, TKV_WAVES_PER_EU))) void tkv_decode_kernel(
     const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map, const uint16_t *__restrict__ q,
     const int32_t *__restrict__ page_indptr, const int32_t *__restrict__ page_ids,
@@ -470,8 +550,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     float kappa, float *__restrict__ acc_ws, float *__restrict__ ml_ws, int32_t *status
     )
 {
-    __shared__ Lds lds;
-    __shared__ float qf[8][kHeadDim];
+    using QF = typename std::conditional<KC, _Float16, float>::type;   // q * 2^E is exact in either type
+    __shared__ Lds<KC> lds;
+    __shared__ QF qf[8][kHeadDim];
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
@@ -501,7 +582,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     // 2^E with max|q| * 2^E in [2^14, 2^15); E clamped so every factor stays a normal fp32
     int ex = 0;
     if (amax > 0.0f) { (void)frexpf(amax, &ex); }   // amax = m * 2^ex, m in [0.5, 1)
-    int E = 15 - ex;
+    int E = (KC ? kKcQExp : 15) - ex;
     E = E > 100 ? 100 : (E < -100 ? -100 : E);
     if (!(amax > 0.0f)) E = 0;
     const float two_e = ldexpf(1.0f, E);
@@ -511,10 +592,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     lc.negk = r16 >= 8 ? -1.0f : 0.0f;
     lc.lomask = r16 >= 8 ? 0xffffffffu : 0u;
     lc.vmul01 = lc.vmul23 = 0;
+    lc.zmul = r16 >= 8 ? 0.0f : 0x1p-24f;
     // q * 2^E to LDS; per-group sums of the unscaled q: lanes 16g .. 16g+15 hold group g
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
-        reinterpret_cast<float2 *>(qf[h])[lane] = make_float2(qv[h][0] * two_e, qv[h][1] * two_e);
+        if constexpr (KC) reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(qv[h][0] * two_e, qv[h][1] * two_e);
+        else reinterpret_cast<float2 *>(qf[h])[lane] = make_float2(qv[h][0] * two_e, qv[h][1] * two_e);
         float sum = qv[h][0] + qv[h][1];
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o);
@@ -551,16 +634,21 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     // INT2 pages of the range, then INT4 pages: each page runs one dequantisation path
     const int e2 = pe < np2 ? pe : np2;
     if (pb < e2) {
-        build_q_operand<2>(qf[hcol], q4, lane, lds);
+        build_q_operand<2, KC>(qf[hcol], q4, lane, lds);
+        LaneConst lc2 = lc;
+        if constexpr (KC) {
+            lc2.kappa = lc.kappa * lc.F;   // the power of two that the K scale carries otherwise
+            lds.kc_nil()[lane & 31] = make_uint4(0u, 0u, 0u, 0u);
+        }
         lds_order();
-        run_pages<2>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
-                     n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
+        run_pages<2, KC>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
+                         n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc2, st, lds, status);
     }
     const int b4 = pb > np2 ? pb : np2;
     if (b4 < pe) {
-        build_q_operand<4>(qf[hcol], q4, lane, lds);
+        build_q_operand<4, KC>(qf[hcol], q4, lane, lds);
         lds_order();
-        run_pages<4>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
+        run_pages<4, KC>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
                      n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
     }
 
@@ -658,7 +746,8 @@ int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_
     float *acc_ws = (float *)workspace;
     float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     const float kappa = sm_scale * 1.44269504088896340736f;
-    hipLaunchKernelGGL(tkv_decode_kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64), 0,
+    auto kernel = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL ? tkv_decode_kernel<true> : tkv_decode_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(n_items * desc->n_kv_heads)), dim3(64), 0,
                        (hipStream_t)stream, (const uint8_t *)pool, bit_map, (const uint16_t *)q, page_indptr,
                        page_ids, n_tok_int2, n_tok_int4, items, batch, desc->n_kv_heads, n_q_heads,
                        desc->n_pages_int2, desc->n_pages_int4, kappa, acc_ws, ml_ws, status

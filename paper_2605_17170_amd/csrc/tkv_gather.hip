@@ -46,6 +46,15 @@ __device__ __forceinline__ uint4 dequant8(uint32_t lo, uint32_t hi, _Float16 s, 
                       __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(code_pair<0>(hi), sv, zv)),
                       __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(code_pair<2>(hi), sv, zv)));
 }
+// The same with one (scale, zero) pair per code: s01 .. s67 and z01 .. z67 are fp16 pairs in code order.
+__device__ __forceinline__ uint4 dequant8_each(uint32_t lo, uint32_t hi, const uint32_t (&sp)[4], const uint32_t (&zp)[4])
+{
+    auto f = [](half2_t c, uint32_t s, uint32_t z) {
+        return __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(c, __builtin_bit_cast(half2_t, s), __builtin_bit_cast(half2_t, z)));
+    };
+    return make_uint4(f(code_pair<0>(lo), sp[0], zp[0]), f(code_pair<2>(lo), sp[1], zp[1]),
+                      f(code_pair<0>(hi), sp[2], zp[2]), f(code_pair<2>(hi), sp[3], zp[3]));
+}
 // Eight consecutive sub-byte codes starting at bit `shift` of w -> one code per byte.
 template <int BITS> __device__ __forceinline__ void spread8(uint32_t w, int shift, uint32_t &lo, uint32_t &hi)
 {
@@ -56,7 +65,8 @@ template <int BITS> __device__ __forceinline__ void spread8(uint32_t w, int shif
          (((v >> (7 * BITS)) & m) << 24);
 }
 
-template <int BITS>
+// KC: the keys of this (INT2) record are quantised per channel over blocks of 32 slots.
+template <int BITS, bool KC>
 __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, uint16_t *__restrict__ K_out,
                                               uint16_t *__restrict__ V_out, int dst, bool valid, int head,
                                               int n_kv_heads, uint8_t (*codes)[kHeadDim], uint16_t *vmeta)
@@ -99,10 +109,28 @@ __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, u
         // INT4: chunk (tile*4 + part)*16 + row = word `part` (8 channels) of the four groups
         // INT2: chunk (tile*2 + part/2)*16 + row = word part/2 (16 channels); this thread takes half part%2
         const uint4 kw = BITS == 4 ? kc[(tile * 4 + part) * 16 + row] : kc[(tile * 2 + (part >> 1)) * 16 + row];
-        const uint2 ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[slot];
-        const uint2 kzc = reinterpret_cast<const uint2 *>(rec + R::kKZero)[slot];
         const uint32_t w[4] = {kw.x, kw.y, kw.z, kw.w};
         uint4 *out = reinterpret_cast<uint4 *>(K_out + ((size_t)dst * n_kv_heads + head) * kHeadDim);
+        if constexpr (KC) {
+            // channels 32*i + 8*part + j: chunks (block, group i, quarter 2*(part/2) + j/4) of the planes, fp16
+            // half part%2 of word j%4.  Each plane is 1 KiB per record and stays in cache.
+            const uint4 *sp4 = reinterpret_cast<const uint4 *>(rec + R::kKScale) + (slot >> 5) * 16 + 2 * (part >> 1);
+            const uint4 *zp4 = reinterpret_cast<const uint4 *>(rec + R::kKZero) + (slot >> 5) * 16 + 2 * (part >> 1);
+            const uint32_t sel = (part & 1) ? 0x07060302u : 0x05040100u;   // v_perm: the chosen halves of (second, first)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint4 s0 = sp4[4 * i], s1 = sp4[4 * i + 1], z0 = zp4[4 * i], z1 = zp4[4 * i + 1];
+                const uint32_t sp[4] = {__builtin_amdgcn_perm(s0.y, s0.x, sel), __builtin_amdgcn_perm(s0.w, s0.z, sel),
+                                        __builtin_amdgcn_perm(s1.y, s1.x, sel), __builtin_amdgcn_perm(s1.w, s1.z, sel)};
+                const uint32_t zp[4] = {__builtin_amdgcn_perm(z0.y, z0.x, sel), __builtin_amdgcn_perm(z0.w, z0.z, sel),
+                                        __builtin_amdgcn_perm(z1.y, z1.x, sel), __builtin_amdgcn_perm(z1.w, z1.z, sel)};
+                uint32_t lo, hi;
+                spread8<BITS>(w[i], 16 * (part & 1), lo, hi);
+                out[4 * i + part] = dequant8_each(lo, hi, sp, zp);
+            }
+        } else {
+        const uint2 ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[slot];
+        const uint2 kzc = reinterpret_cast<const uint2 *>(rec + R::kKZero)[slot];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t sc = i < 2 ? ksc.x : ksc.y, zc = i < 2 ? kzc.x : kzc.y;
@@ -111,6 +139,7 @@ __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, u
             uint32_t lo, hi;
             spread8<BITS>(w[i], BITS == 4 ? 0 : 16 * (part & 1), lo, hi);
             out[4 * i + part] = dequant8(lo, hi, s, z);
+        }
         }
     }
     __syncthreads();
@@ -128,6 +157,7 @@ __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, u
     }
 }
 
+template <bool KC>
 __global__ __launch_bounds__(256) void tkv_gather_kernel(
     const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map, const int32_t *__restrict__ work_pages,
     const int32_t *__restrict__ work_dst, int n_kv_heads, int n_pages_int2, int n_pages_int4,
@@ -151,8 +181,8 @@ __global__ __launch_bounds__(256) void tkv_gather_kernel(
     const bool valid = dst >= 0 && dst < n_tokens;
     if (dst >= n_tokens && status && (threadIdx.x & 3) == 0) atomicOr(status, TKV_STATUS_DST_RANGE);
     const uint8_t *rec = pool + record_offset(page, head, n_kv_heads, n_pages_int2);
-    if (bits == 2) gather_record<2>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
-    else gather_record<4>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
+    if (bits == 2) gather_record<2, KC>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
+    else gather_record<4, false>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
 }
 
 } // namespace
@@ -162,7 +192,8 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
                       int32_t *status, void *stream)
 {
     const dim3 grid((unsigned)(n_work * desc->n_kv_heads)), block(256);
-    hipLaunchKernelGGL(tkv_gather_kernel, grid, block, 0, (hipStream_t)stream, (const uint8_t *)pool, bit_map,
+    auto kernel = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL ? tkv_gather_kernel<true> : tkv_gather_kernel<false>;
+    hipLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)stream, (const uint8_t *)pool, bit_map,
                        work_pages, work_dst, desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4,
                        (uint16_t *)K_out, (uint16_t *)V_out, n_tokens, status);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;

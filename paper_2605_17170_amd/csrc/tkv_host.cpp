@@ -23,7 +23,8 @@ bool desc_ok(const tkv_desc *d)
 {
     return d && d->n_kv_heads > 0 && d->head_dim == kHeadDim && d->group_size == kGroup &&
            d->page_tokens == kPageTokens && d->n_pages_int2 >= 0 && d->n_pages_int4 >= 0 &&
-           (int64_t)d->n_pages_int2 + d->n_pages_int4 <= INT32_MAX / kPageTokens;
+           (int64_t)d->n_pages_int2 + d->n_pages_int4 <= INT32_MAX / kPageTokens &&
+           (d->int2_key_axis == TKV_KEYS_PER_TOKEN || d->int2_key_axis == TKV_KEYS_PER_CHANNEL);
 }
 
 int desc_status(const tkv_desc *d)
@@ -227,6 +228,23 @@ int32_t tkv_seq_page_ids(const tkv_seq *s, int32_t *out, int32_t capacity)
 
 /* ---------------------------------------------------------------- Q1: append plan */
 
+int tkv_route_residual(const uint8_t *tag_bits, int32_t n_tokens, uint8_t *bits_out)
+{
+    if (n_tokens < 0 || (n_tokens > 0 && (!tag_bits || !bits_out))) return TKV_ERR_INVALID_ARG;
+    int32_t n2 = 0;
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        if (tag_bits[t] != 2 && tag_bits[t] != 4) return TKV_ERR_BAD_BITS;
+        n2 += tag_bits[t] == 2;
+    }
+    int32_t keep = n2 - n2 % kGroup;   // INT2 tokens that fill whole blocks, counted from the front
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        uint8_t b = tag_bits[t];
+        if (b == 2 && keep-- <= 0) b = 4;
+        bits_out[t] = b;
+    }
+    return TKV_OK;
+}
+
 int32_t tkv_plan_append_max_work(int32_t n_tokens)
 {
     if (n_tokens < 0) return TKV_ERR_INVALID_ARG;
@@ -248,6 +266,7 @@ int tkv_plan_append(tkv_alloc *a, tkv_seq *s, const uint8_t *tag_bits, int32_t n
         if (tag_bits[t] != 2 && tag_bits[t] != 4) return TKV_ERR_BAD_BITS;
         ++n_new[tag_bits[t] == 4];
     }
+    if (a->desc.int2_key_axis == TKV_KEYS_PER_CHANNEL && n_new[0] % kGroup) return TKV_ERR_INVALID_ARG;
     int32_t room[2], new_pages[2], touched = 0;
     for (int p = 0; p < 2; ++p) {
         room[p] = (int32_t)s->pages[p].size() * kPageTokens - s->n_tok[p];   // free slots of the open page
@@ -308,6 +327,7 @@ int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page
     int64_t total = 0;
     for (int32_t b = 0; b < batch; ++b) {
         if (n_tok_int2[b] < 0 || n_tok_int4[b] < 0) return TKV_ERR_INVALID_ARG;
+        if (desc->int2_key_axis == TKV_KEYS_PER_CHANNEL && n_tok_int2[b] % kGroup) return TKV_ERR_INVALID_ARG;
         const int32_t p2 = ceil_div(n_tok_int2[b], kPageTokens), p4 = ceil_div(n_tok_int4[b], kPageTokens);
         if (page_indptr[b + 1] - page_indptr[b] != p2 + p4) return TKV_ERR_INVALID_ARG;
         total += kCost2 * p2 + kCost4 * p4;

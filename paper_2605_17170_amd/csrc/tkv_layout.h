@@ -42,5 +42,15 @@ __host__ __device__ inline int vmeta_index(int t, int g)
     return ((((t >> 5) * 4 + ((t & 15) >> 2)) * 4 + g) << 3) + (((t >> 4) & 1) << 2) + (t & 3);
 }
 
+// fp16 index of (block blk = t/32, channel c) in the K scale / K zero planes of an INT2 page whose keys are
+// quantised per channel: 128 positions per block, in chunks of 8 per (group c/32, quarter); a chunk is what
+// one lane of the decode kernel's q operand holds: the pair (c, c+8) of k = c%4 at 2k, 2k+1.
+__host__ __device__ inline int kcmeta_index(int blk, int c)
+{
+    const int g = c >> 5, r = c & 31;
+    const int quarter = 2 * (r >> 4) + ((r & 7) >> 2);
+    return ((((blk * 4 + g) * 4 + quarter) << 3) + 2 * (r & 3) + ((r & 15) >> 3));
+}
+
 } // namespace tkv
 #endif

@@ -25,15 +25,18 @@ class PagedCache:
     """Pool + page tables of one layer for a batch of sequences."""
 
     def __init__(self, n_kv_heads: int, seq_bits: list, device, pool_factor: float = 1.0, shuffle_seed: int = 1,
-                 fill: int | None = None):
+                 fill: int | None = None, key_axis: int = tkv.TKV_KEYS_PER_TOKEN):
         self.device = torch.device(device)
         self.n_kv_heads = n_kv_heads
         self.seq_bits = [np.ascontiguousarray(b, np.uint8) for b in seq_bits]
+        if key_axis == tkv.TKV_KEYS_PER_CHANNEL:
+            # INT2 keys per channel need whole blocks of 32 tokens: the library moves the rest to INT4
+            self.seq_bits = [tkv.tkv_route_residual(b) for b in self.seq_bits]
         need2 = sum(math.ceil(int((b == 2).sum()) / PAGE) for b in self.seq_bits)
         need4 = sum(math.ceil(int((b == 4).sum()) / PAGE) for b in self.seq_bits)
         self.P2 = max(1, int(math.ceil(need2 * pool_factor)))
         self.P4 = max(1, int(math.ceil(need4 * pool_factor)))
-        self.desc = tkv.tkv_desc.make(n_kv_heads, self.P2, self.P4)
+        self.desc = tkv.tkv_desc.make(n_kv_heads, self.P2, self.P4, int2_key_axis=key_axis)
         self.alloc = tkv.tkv_alloc_create(self.desc, shuffle_seed)
         self.seqs = [tkv.tkv_seq_create() for _ in self.seq_bits]
         nbytes = tkv.tkv_pool_bytes(self.desc)

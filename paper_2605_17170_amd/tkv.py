@@ -26,6 +26,9 @@ TKV_STATUS_TAG_MISMATCH = 1
 TKV_STATUS_BITMAP_MISMATCH = 2
 TKV_STATUS_PAGE_RANGE = 4
 TKV_STATUS_DST_RANGE = 8
+TKV_STATUS_BLOCK_PARTIAL = 16
+TKV_KEYS_PER_TOKEN = 0
+TKV_KEYS_PER_CHANNEL = 1
 
 PAGE_TOKENS = 64
 HEAD_DIM = 128
@@ -35,7 +38,7 @@ EXPORTS = [
     "tkv_strerror", "tkv_record_bytes", "tkv_page_bytes", "tkv_pool_bytes", "tkv_record_offset",
     "tkv_alloc_create", "tkv_alloc_destroy", "tkv_alloc_pages", "tkv_free_pages", "tkv_alloc_free_count",
     "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
-    "tkv_seq_page_ids", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
+    "tkv_seq_page_ids", "tkv_route_residual", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
     "tkv_decode_split", "tkv_decode_reduce", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
 ]
@@ -49,12 +52,13 @@ class TkvError(RuntimeError):
 
 class tkv_desc(C.Structure):
     _fields_ = [("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("group_size", C.c_int32),
-                ("page_tokens", C.c_int32), ("n_pages_int2", C.c_int32), ("n_pages_int4", C.c_int32)]
+                ("page_tokens", C.c_int32), ("n_pages_int2", C.c_int32), ("n_pages_int4", C.c_int32),
+                ("int2_key_axis", C.c_int32)]
 
     @classmethod
     def make(cls, n_kv_heads, n_pages_int2, n_pages_int4, head_dim=HEAD_DIM, group_size=GROUP_SIZE,
-             page_tokens=PAGE_TOKENS):
-        return cls(n_kv_heads, head_dim, group_size, page_tokens, n_pages_int2, n_pages_int4)
+             page_tokens=PAGE_TOKENS, int2_key_axis=0):
+        return cls(n_kv_heads, head_dim, group_size, page_tokens, n_pages_int2, n_pages_int4, int2_key_axis)
 
 
 _lib = None
@@ -98,6 +102,8 @@ def lib():
         L.tkv_seq_page_ids.argtypes = [vp, vp, i32]
         L.tkv_plan_append_max_work.restype = i32
         L.tkv_plan_append_max_work.argtypes = [i32]
+        L.tkv_route_residual.restype = C.c_int
+        L.tkv_route_residual.argtypes = [vp, i32, vp]
         L.tkv_plan_append.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, C.POINTER(i32)]
         L.tkv_quantize_append.argtypes = [dp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.tkv_gather_dequant.restype = C.c_int
@@ -225,6 +231,15 @@ def tkv_seq_page_ids(s) -> np.ndarray:
 
 
 # ---------------------------------------------------------------- Q1 (host)
+def tkv_route_residual(tag_bits) -> np.ndarray:
+    """Per-token widths after the residual policy of per-channel INT2 keys (u8[n])."""
+    bits, pb = _np(tag_bits, np.uint8)
+    out = np.empty(bits.size, np.uint8)
+    _check(lib().tkv_route_residual(pb, bits.size, C.c_void_p(out.ctypes.data if bits.size else None)),
+           "tkv_route_residual")
+    return out
+
+
 def tkv_plan_append_max_work(n_tokens: int) -> int:
     return _check(lib().tkv_plan_append_max_work(n_tokens), "tkv_plan_append_max_work")
 

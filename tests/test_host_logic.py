@@ -266,3 +266,46 @@ def test_gather_dequant_validates_before_launch():
     bad = tkv.tkv_desc.make(8, 4, 4)
     bad.head_dim = 64
     assert L.tkv_gather_dequant(C.byref(bad), p, p, p, p, 0, p, p, 0, None, None) != tkv.TKV_OK
+
+
+def test_residual_routing_matches_the_oracle_and_keeps_blocks_whole(oracle):
+    """Residual policy of per-channel INT2 keys (Sec. 3.2.1): the library's rewrite against the oracle's."""
+    rng = np.random.default_rng(31)
+    for _ in range(200):
+        n = int(rng.integers(0, 400))
+        b = rng.choice([2, 4], n, p=[0.7, 0.3]).astype(np.uint8)
+        got = tkv.tkv_route_residual(b)
+        assert np.array_equal(got, oracle.route_residual(b))
+        assert int((got == 2).sum()) % 32 == 0
+    assert tkv.tkv_route_residual(np.uint8([2] * 31)).tolist() == [4] * 31
+    with pytest.raises(tkv.TkvError) as e:
+        tkv.tkv_route_residual(np.uint8([2, 3]))
+    assert e.value.status == tkv.TKV_ERR_BAD_BITS
+    # in place
+    b = np.uint8([2] * 40)
+    p = C.c_void_p(b.ctypes.data)
+    assert tkv.lib().tkv_route_residual(p, 40, p) == tkv.TKV_OK and b.tolist() == [2] * 32 + [4] * 8
+
+
+def test_per_channel_key_mode_is_validated():
+    d = tkv.tkv_desc.make(2, 4, 4, int2_key_axis=tkv.TKV_KEYS_PER_CHANNEL)
+    assert tkv.tkv_pool_bytes(d) == tkv.tkv_pool_bytes(tkv.tkv_desc.make(2, 4, 4))      # same record size
+    bad = tkv.tkv_desc.make(2, 4, 4, int2_key_axis=2)
+    assert tkv.tkv_pool_bytes(bad) == 0
+    h = C.c_void_p()
+    assert tkv.lib().tkv_alloc_create(C.byref(bad), 0, C.byref(h)) == tkv.TKV_ERR_BAD_SHAPE
+    a, s = tkv.tkv_alloc_create(d, 0), tkv.tkv_seq_create()
+    with pytest.raises(tkv.TkvError) as e:
+        tkv.tkv_plan_append(a, s, np.uint8([2] * 33))            # INT2 tokens must come in blocks of 32
+    assert e.value.status == tkv.TKV_ERR_INVALID_ARG
+    assert tkv.tkv_seq_n_tokens(s, 2) == 0 and tkv.tkv_alloc_free_count(a, 2) == 4
+    slots, wp, ws = tkv.tkv_plan_append(a, s, tkv.tkv_route_residual(np.uint8([2] * 33)))
+    assert tkv.tkv_seq_n_tokens(s, 2) == 32 and tkv.tkv_seq_n_tokens(s, 4) == 1
+    # decode plan: an INT2 token count that is not a multiple of 32 cannot come from this mode
+    ip = np.int32([0, 1])
+    with pytest.raises(tkv.TkvError):
+        tkv.tkv_plan_decode(d, ip, np.int32([33]), np.int32([0]), 1)
+    items, sip = tkv.tkv_plan_decode(d, ip, np.int32([32]), np.int32([0]), 1)
+    assert items.tolist() == [[0, 0, 1, 0]]
+    tkv.tkv_seq_destroy(s)
+    tkv.tkv_alloc_destroy(a)
