@@ -297,43 +297,45 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         // MFMAs.  Lanes of the hi columns read their "rounded product to subtract" from a plane of zeros.
         const uint4 *sxp = r16 >= 8 ? lds.kc_scale() : lds.kc_nil();
         const uint32_t rot = (q4 & 1) ? 5u : 29u;   // this lane's 16 codes of a word are its upper / lower half
+        // operands of both blocks first: the zero-term chains run on the matrix core while the VALU forms q s
+        floatx4 z[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        uint32_t b[2][4][4];
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            floatx4 z = {0.f, 0.f, 0.f, 0.f};
-            uint32_t b[4][4];
+        for (int g = 0; g < 4; ++g) {
+            const uint4 qp = lds.qp[g][lane], qo = lds.qo[g][lane];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int blk = 0; blk < 2; ++blk) {
                 const int mi = (blk * 4 + g) * 4 + q4;
                 const uint4 zc = lds.kc_zero()[mi];
-                const uint4 qp = lds.qp[g][lane];
-                z = mfma(as_half8(zc.x, zc.y, zc.z, zc.w), as_half8(qp.x, qp.y, qp.z, qp.w), z);   // every row: sum_c q_c z_c
-                const uint4 sc = lds.kc_scale()[mi], sx = sxp[mi], qo = lds.qo[g][lane];
-                b[g][0] = pk_rem(qo.x, sc.x, pk_mul(qo.x, sx.x));
-                b[g][1] = pk_rem(qo.y, sc.y, pk_mul(qo.y, sx.y));
-                b[g][2] = pk_rem(qo.z, sc.z, pk_mul(qo.z, sx.z));
-                b[g][3] = pk_rem(qo.w, sc.w, pk_mul(qo.w, sx.w));
+                z[blk] = mfma(as_half8(zc.x, zc.y, zc.z, zc.w), as_half8(qp.x, qp.y, qp.z, qp.w), z[blk]);   // every row: sum_c q_c z_c
+                const uint4 sc = lds.kc_scale()[mi], sx = sxp[mi];
+                b[blk][g][0] = pk_rem(qo.x, sc.x, pk_mul(qo.x, sx.x));
+                b[blk][g][1] = pk_rem(qo.y, sc.y, pk_mul(qo.y, sx.y));
+                b[blk][g][2] = pk_rem(qo.z, sc.z, pk_mul(qo.z, sx.z));
+                b[blk][g][3] = pk_rem(qo.w, sc.w, pk_mul(qo.w, sx.w));
             }
-            z *= lc.zmul;   // to the unit of the code products, once per head (hi columns only)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                const int e = 2 * blk + t2;
-                const uint32_t w[4] = {pr.kw[e].x, pr.kw[e].y, pr.kw[e].z, pr.kw[e].w};
-                floatx4 sacc = z;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    // fields at bits 4:3, 6:5, 8:7, 10:9 of each half: q s spans more binades than q, and
-                    // the matrix core drops product bits that fall below its alignment window
-                    const uint32_t ws = __builtin_amdgcn_alignbit(w[g], w[g], rot);   // w >> 5 or w << 3, stray bits fall outside the masks
-                    const half8 a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
-                    sacc = mfma(a, as_half8(b[g][0], b[g][1], b[g][2], b[g][3]), sacc);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sacc[i] += row_ror8(sacc[i]);
-                asm volatile("" : "+v"(sacc));
-                S[e] = sacc;
-            }
-            __builtin_amdgcn_sched_barrier(0);   // one block's operands at a time (register pressure)
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S[e] = z[e >> 1] * lc.zmul;   // to the unit of the code products, hi columns only
+        // four independent accumulation chains (one per 16-token tile)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t wg = g == 0 ? pr.kw[e].x : g == 1 ? pr.kw[e].y : g == 2 ? pr.kw[e].z : pr.kw[e].w;
+                // fields at bits 4:3, 6:5, 8:7, 10:9 of each half: q s spans more binades than q, and
+                // the matrix core drops product bits that fall below its alignment window
+                const uint32_t ws = __builtin_amdgcn_alignbit(wg, wg, rot);   // w >> 5 or w << 3, stray bits fall outside the masks
+                const half8 a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
+                S[e] = mfma(a, as_half8(b[e >> 1][g][0], b[e >> 1][g][1], b[e >> 1][g][2], b[e >> 1][g][3]), S[e]);
+            }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[e][i] += row_ror8(S[e][i]);   // the two pieces of q s: columns h and h + 8
+            asm volatile("" : "+v"(S[e]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
     } else
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -552,7 +554,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
 {
     using QF = typename std::conditional<KC, _Float16, float>::type;   // q * 2^E is exact in either type
     __shared__ Lds<KC> lds;
-    __shared__ QF qf[8][kHeadDim];
+    // q * 2^E per head and channel, read while the MFMA operands are built.  The per-channel-key kernel keeps it
+    // (2 KiB of fp16) in the page staging area ks | vs | vz, which is idle then, so that twelve wavefronts
+    // still fit the LDS of a compute unit; it is written again before the INT4 operand is built.
+    __shared__ QF qf_own[KC ? 1 : 8][kHeadDim];
+    QF(*qf)[kHeadDim] = KC ? reinterpret_cast<QF(*)[kHeadDim]>(lds.ks) : qf_own;
+    static_assert(sizeof(lds.ks) + sizeof(lds.vs) + sizeof(lds.vz) >= 8 * kHeadDim * sizeof(_Float16) && sizeof(lds.ks) % 16 == 0 &&
+                  sizeof(lds.vs) % 16 == 0, "ks, vs, vz are consecutive members and together hold q for 8 heads");
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
@@ -646,6 +654,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     }
     const int b4 = pb > np2 ? pb : np2;
     if (b4 < pe) {
+        if constexpr (KC) {
+            if (pb < e2) {   // the INT2 pages have used the staging area since
+                lds_order();
+#pragma unroll
+                for (int h = 0; h < 8; ++h) {
+                    uint32_t two = 0;
+                    if (h < R) two = reinterpret_cast<const uint32_t *>(q + ((size_t)seq * n_q_heads + kvh * R + h) * kHeadDim)[lane];
+                    reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(__uint_as_float(two << 16) * two_e, __uint_as_float(two & 0xffff0000u) * two_e);
+                }
+                lds_order();
+            }
+        }
         build_q_operand<4, KC>(qf[hcol], q4, lane, lds);
         lds_order();
         run_pages<4, KC>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
