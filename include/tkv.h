@@ -262,7 +262,8 @@ int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bi
  * sequence's page list (INT2 pages first).  Items are balanced by decode cost:
  * an INT2 page weighs 6, an INT4 page 7 (measured kernel time per page).
  *   page_indptr   host i32[batch+1], page-list offsets of the sequences
- *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial)
+ *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial;
+ *                 with TKV_KEYS_PER_CHANNEL n_tok_int2 must be a multiple of 32)
  *   target_items  wanted number of items over the whole batch (>= 1)
  *   items_out     host i32[4*capacity]: {sequence, first page, end page, 0},
  *                 page indices relative to the sequence's list
@@ -296,7 +297,10 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
  *   status         device i32, may be NULL
  * Preconditions on the cache contents (not checked): stored scales and zeros
  * finite; V scales up to 255 are used exactly, larger ones saturate at 255
- * (the kernel forms softmax weight x V scale in fp16 and keeps it finite).
+ * (the kernel forms softmax weight x V scale in fp16 and keeps it finite);
+ * with TKV_KEYS_PER_CHANNEL the scales of the INT2 keys likewise up to 1023
+ * (the kernel forms q x K scale in fp16), and every n_tok_int2 is a multiple
+ * of 32.
  * n_q_heads / n_kv_heads must be 1, 2, 4 or 8.  Two launches on `stream`:
  * the split kernel, then the cross-split reduction.
  */
