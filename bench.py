@@ -227,6 +227,24 @@ def main():
         "kv_bytes_per_step": kc_bytes, "int4_token_share": float((kc.tag_bits == 4).mean()),
         "append_ms": float(np.median(kc_app)), "prefill_gather_ms": float(np.median(kc_gat)),
         "note": "same workload, tkv_desc.int2_key_axis = per channel; same cold-pool protocol"}
+    # ---- decode-phase append: one generated token per sequence written at INT4 into the open page
+    small = harness.PagedCache(w.n_kv_heads, [np.full(100, 4, np.uint8)] * w.batch, dev, pool_factor=2.0)
+    t0 = time.perf_counter()
+    plans = [tkv.tkv_plan_append(small.alloc, s, np.uint8([4]), b) for b, s in enumerate(small.seqs)]
+    plan1_us = (time.perf_counter() - t0) * 1e6
+    wp1 = torch.from_numpy(np.concatenate([p[1] for p in plans])).to(dev)
+    ws1 = torch.from_numpy(np.concatenate([p[2] for p in plans])).to(dev)
+    b1 = torch.full((w.batch,), 4, dtype=torch.uint8, device=dev)
+    one_per, _ = time_steps(lambda i: tkv.tkv_quantize_append(small.desc, small.pool, small.bit_map, dK[:w.batch], dV[:w.batch],
+                                                              b1, wp1, ws1, small.status), 50, 5)
+    assert int(small.status.item()) == 0
+    res["decode_phase_append"] = {"us_per_step": float(np.median(one_per)) * 1e3, "plan_host_us": plan1_us,
+                                  "note": "tkv_quantize_append of one new INT4 token per sequence (%d sequences, %d kv heads), "
+                                          "interval between back-to-back launches through the Python binding (bounded below by the host's call "
+                                          "overhead; the kernel's own duration is in the rocprofv3 kernel trace); host planning of the %d "
+                                          "single-token appends beside it"
+                                          % (w.batch, w.n_kv_heads, w.batch)}
+    small.close()
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(w, q, K, V)
     print(json.dumps(res))
