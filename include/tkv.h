@@ -132,6 +132,34 @@ int32_t tkv_seq_n_pages(const tkv_seq *s, int bits);
 int32_t tkv_seq_page_ids(const tkv_seq *s, int32_t *out, int32_t capacity);
 
 /* ------------------------------------------------------------------ */
+/* T1: triaxial tagger and tag -> bitwidth lookup (host).               */
+/* ------------------------------------------------------------------ */
+/*
+ * A token's tag is a point of temporal x modal x semantic (Sec. 3.1):
+ *   semantic  0 inst, 1 user, 2 assistant, 3 reasoning, 4 tool_call, 5 obs, 6 delim
+ *   modal     0 text, 1 image
+ *   temporal  0 older, 1 turn_m2, 2 turn_m1, 3 current
+ * tag code = (temporal * 2 + modal) * 7 + semantic, 56 codes (TKV_N_TAGS).
+ * tkv_tag_tokens derives the temporal axis in one scan from the per-token
+ * semantic role and modality that the chat template gives (host, u8[n_tokens]
+ * each): a turn runs from one user message up to, not including, the next;
+ * a user message starts at a `user` token that does not follow a `user`
+ * token; tokens before the first user message are turn 0.  tags_out: host
+ * u8[n_tokens].  TKV_ERR_INVALID_ARG on a null array or an axis value out of
+ * range (nothing is written then).
+ * tkv_tags_to_bits looks every tag up in the calibrated map b*: S -> {2, 4}
+ * (table, host u8[56]) and yields the per-token bitwidth array that
+ * tkv_plan_append and tkv_quantize_append take (Sec. 3.2.3, "Tagging").
+ * TKV_ERR_INVALID_ARG on a tag >= 56, TKV_ERR_BAD_BITS on a table entry other
+ * than 2 or 4.  tkv_tag_counts adds the tokens of each tag to counts (host
+ * i64[56], the N_k of Eq. 3); the caller zeroes it first.
+ */
+enum { TKV_N_TAGS = 56 };
+int tkv_tag_tokens(const uint8_t *semantic, const uint8_t *modal, int32_t n_tokens, uint8_t *tags_out);
+int tkv_tags_to_bits(const uint8_t *tags, int32_t n_tokens, const uint8_t *table, uint8_t *bits_out);
+int tkv_tag_counts(const uint8_t *tags, int32_t n_tokens, int64_t *counts);
+
+/* ------------------------------------------------------------------ */
 /* A1: tag -> bitwidth allocation (host).                               */
 /* ------------------------------------------------------------------ */
 /*

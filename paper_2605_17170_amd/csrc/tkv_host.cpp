@@ -383,6 +383,44 @@ int tkv_quantize_append(const tkv_desc *desc, void *pool, uint8_t *bit_map,
     return tkv_launch_append(desc, pool, bit_map, K, V, tag_bits, n_tokens, work_pages, work_src, n_work, status, stream);
 }
 
+/* ---------------------------------------------------------------- T1: tagger */
+
+int tkv_tag_tokens(const uint8_t *semantic, const uint8_t *modal, int32_t n_tokens, uint8_t *tags_out)
+{
+    if (n_tokens < 0 || (n_tokens > 0 && (!semantic || !modal || !tags_out))) return TKV_ERR_INVALID_ARG;
+    constexpr uint8_t kUser = 1;
+    for (int32_t t = 0; t < n_tokens; ++t)
+        if (semantic[t] > 6 || modal[t] > 1) return TKV_ERR_INVALID_ARG;
+    // one scan from the end: the number of user messages that start after a token is its distance in turns
+    int32_t later = 0;
+    for (int32_t t = n_tokens - 1; t >= 0; --t) {
+        const int temporal = later > 2 ? 0 : 3 - later;
+        tags_out[t] = (uint8_t)((temporal * 2 + modal[t]) * 7 + semantic[t]);
+        later += semantic[t] == kUser && (t == 0 || semantic[t - 1] != kUser);
+    }
+    return TKV_OK;
+}
+
+int tkv_tags_to_bits(const uint8_t *tags, int32_t n_tokens, const uint8_t *table, uint8_t *bits_out)
+{
+    if (n_tokens < 0 || !table || (n_tokens > 0 && (!tags || !bits_out))) return TKV_ERR_INVALID_ARG;
+    for (int k = 0; k < TKV_N_TAGS; ++k)
+        if (table[k] != 2 && table[k] != 4) return TKV_ERR_BAD_BITS;
+    for (int32_t t = 0; t < n_tokens; ++t)
+        if (tags[t] >= TKV_N_TAGS) return TKV_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < n_tokens; ++t) bits_out[t] = table[tags[t]];
+    return TKV_OK;
+}
+
+int tkv_tag_counts(const uint8_t *tags, int32_t n_tokens, int64_t *counts)
+{
+    if (n_tokens < 0 || !counts || (n_tokens > 0 && !tags)) return TKV_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < n_tokens; ++t)
+        if (tags[t] >= TKV_N_TAGS) return TKV_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < n_tokens; ++t) ++counts[tags[t]];
+    return TKV_OK;
+}
+
 namespace {
 int alloc_args_status(int32_t n_tags, const int64_t *N, const double *D2, const double *D4, double B, const uint8_t *out)
 {

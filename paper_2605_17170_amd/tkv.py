@@ -41,6 +41,7 @@ EXPORTS = [
     "tkv_seq_page_ids", "tkv_route_residual", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
     "tkv_decode_split", "tkv_decode_reduce", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
+    "tkv_tag_tokens", "tkv_tags_to_bits", "tkv_tag_counts",
 ]
 
 
@@ -118,6 +119,9 @@ def lib():
                                            vp, vp, sz, vp, vp]
         L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
         L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.tkv_tag_tokens.argtypes = [vp, vp, i32, vp]
+        L.tkv_tags_to_bits.argtypes = [vp, i32, vp, vp]
+        L.tkv_tag_counts.argtypes = [vp, i32, vp]
         for fn in (L.tkv_allocate_bits_greedy, L.tkv_allocate_bits_exhaustive):
             fn.restype = C.c_int
             fn.argtypes = [i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
@@ -384,3 +388,35 @@ def tkv_allocate_bits_greedy(N, D2, D4, B):
 def tkv_allocate_bits_exhaustive(N, D2, D4, B):
     """Tag bitwidths (2 or 4) by exhaustive search, at most 22 tags; argument marshalling only."""
     return _allocate_bits(lib().tkv_allocate_bits_exhaustive, "tkv_allocate_bits_exhaustive", N, D2, D4, B)
+
+
+# ---------------------------------------------------------------- T1 (host)
+N_TAGS = 56
+
+
+def tkv_tag_tokens(semantic, modal) -> np.ndarray:
+    """Tag codes u8[n] from per-token semantic role and modality (u8[n] each)."""
+    sem, ps = _np(semantic, np.uint8)
+    mod, pm = _np(modal, np.uint8)
+    if sem.shape != mod.shape:
+        raise ValueError("semantic and modal must have one entry per token")
+    out = np.empty(sem.size, np.uint8)
+    _check(lib().tkv_tag_tokens(ps, pm, sem.size, C.c_void_p(out.ctypes.data if sem.size else None)), "tkv_tag_tokens")
+    return out
+
+
+def tkv_tags_to_bits(tags, table) -> np.ndarray:
+    tg, pt = _np(tags, np.uint8)
+    tb, pb = _np(table, np.uint8)
+    if tb.size != N_TAGS:
+        raise ValueError("the table has one entry per tag (56)")
+    out = np.empty(tg.size, np.uint8)
+    _check(lib().tkv_tags_to_bits(pt, tg.size, pb, C.c_void_p(out.ctypes.data if tg.size else None)), "tkv_tags_to_bits")
+    return out
+
+
+def tkv_tag_counts(tags) -> np.ndarray:
+    tg, pt = _np(tags, np.uint8)
+    counts = np.zeros(N_TAGS, np.int64)
+    _check(lib().tkv_tag_counts(pt, tg.size, C.c_void_p(counts.ctypes.data)), "tkv_tag_counts")
+    return counts
