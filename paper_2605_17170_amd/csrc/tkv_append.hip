@@ -41,13 +41,21 @@ template <int BITS>
 __device__ __forceinline__ GroupQ quantize_values(const float (&f)[32])
 {
     constexpr int L = (1 << BITS) - 1;
+    // Inputs are finite, so min / max instructions give the value a chain of comparisons gives; only the sign
+    // of a zero can differ.  A zero minimum is stored as +0 anyway; a zero maximum takes the sign the scalar
+    // definition gives it (the first element that is not below its predecessors' maximum), settled below.
     float mn = f[0], mx = f[0];
 #pragma unroll
     for (int i = 1; i < 32; ++i) {
-        mn = f[i] < mn ? f[i] : mn;
-        mx = f[i] > mx ? f[i] : mx;
+        mn = fminf(mn, f[i]);
+        mx = fmaxf(mx, f[i]);
     }
     if (mn == 0.0f) mn = 0.0f;   // -0 -> +0
+    if (__builtin_expect(mx == 0.0f, 0)) {
+        mx = f[0];
+#pragma unroll
+        for (int i = 1; i < 32; ++i) mx = f[i] > mx ? f[i] : mx;
+    }
     const float r = __fsub_rn(mx, mn);
     const float s32 = __fdiv_rn(r, (float)L);
     const __half sh = __float2half_rn(s32), zh = __float2half_rn(mn);
@@ -55,22 +63,31 @@ __device__ __forceinline__ GroupQ quantize_values(const float (&f)[32])
     GroupQ out;
     out.scale = __half_as_ushort(sh);
     out.zero = __half_as_ushort(zh);
-    const float inv = s == 0.0f ? 0.0f : __fdiv_rn(1.0f, s);
+    const float inv = s == 0.0f ? 0.0f : __fdiv_rn(1.0f, s);   // a zero scale gives t = 0 and code 0 for every element
+    // clamp, then round by adding 1.5 * 2^23: the sum is rounded to an integer (nearest, ties to even, the
+    // same result as rounding first and clamping after) and its bit pattern is kBias + code
+    constexpr float kMagic = 12582912.0f;
+    constexpr uint32_t kBias = 0x4b400000u;
     uint32_t c[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
-        float t = rintf(__fmul_rn(__fsub_rn(f[i], z), inv));
-        t = fminf(fmaxf(t, 0.0f), (float)L);
-        c[i] = s == 0.0f ? 0u : (uint32_t)(int)t;
+        const float t = __builtin_amdgcn_fmed3f(__fmul_rn(__fsub_rn(f[i], z), inv), 0.0f, (float)L);
+        c[i] = __float_as_uint(__fadd_rn(t, kMagic));
     }
-#pragma unroll
-    for (int w = 0; w < 4; ++w) out.words[w] = 0;
+    // packed by shift-and-add; what the biases add up to (modulo 2^32) is one constant per word
     constexpr int per_word = 32 / BITS;
+    uint32_t bias_word = 0, bias_byte = 0;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) out.words[i / per_word] |= c[i] << (BITS * (i % per_word));
+    for (int i = 0; i < per_word; ++i) bias_word += kBias << (BITS * i);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bias_byte += kBias << (8 * k);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) out.words[w] = 0u - bias_word;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) out.words[i / per_word] += c[i] << (BITS * (i % per_word));
 #pragma unroll
     for (int w = 0; w < 8; ++w)
-        out.bytes[w] = c[4 * w] | (c[4 * w + 1] << 8) | (c[4 * w + 2] << 16) | (c[4 * w + 3] << 24);
+        out.bytes[w] = c[4 * w] + (c[4 * w + 1] << 8) + (c[4 * w + 2] << 16) + (c[4 * w + 3] << 24) - bias_byte;
     return out;
 }
 
@@ -135,7 +152,7 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
         dst[0] = make_uint4(vq.bytes[0], vq.bytes[1], vq.bytes[2], vq.bytes[3]);
         dst[1] = make_uint4(vq.bytes[4], vq.bytes[5], vq.bytes[6], vq.bytes[7]);
     }
-    __syncthreads();
+    const bool page_full = __syncthreads_and(valid);   // every slot of the page arrives in this call
     if constexpr (KC) {
         // thread (block, channel): the block's 32 token values of one channel are one quantisation group
         {
@@ -180,6 +197,44 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(lds_codes);
     uint32_t *vc = reinterpret_cast<uint32_t *>(rec + R::kVCodes);
     constexpr int n_words = R::kCodeBytes / 4;
+    if (page_full) {
+        // Whole page: a thread transposes four adjacent channels x the (8 | 16) tokens of one word with 32-bit
+        // LDS reads (a row of the byte tile holds the token's codes in channel order), merges 2 | 4 tokens per
+        // byte and finishes with a 4 x 4 byte transpose; no read-modify-write.
+        constexpr int n_units = n_words / 4;   // 256 (INT4) / 128 (INT2)
+        if (tid < n_units) {
+            const int k = tid & 3, n4 = (tid >> 2) & 3, quad = (tid >> 4) & 3, h = (tid >> 6) & 1;
+            const int blk = tid >> 7;   // INT4 only (0 for INT2)
+            const int c0 = 64 * h + 16 * k + 4 * n4;
+            uint32_t m[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                m[b] = 0;
+#pragma unroll
+                for (int e = 0; e < 8 / BITS; ++e) {
+                    const int p = (8 / BITS) * b + e;   // position of the token in the word
+                    int t;
+                    if (BITS == 4) {
+                        const int j = 2 * (p & 3) + (p >> 2);
+                        t = 32 * blk + 16 * (j >> 2) + 4 * quad + (j & 3);
+                    } else {
+                        const int j = 2 * (p & 3) + (p >> 3);
+                        t = 32 * ((p & 7) >> 2) + 16 * (j >> 2) + 4 * quad + (j & 3);
+                    }
+                    m[b] |= *reinterpret_cast<const uint32_t *>(codes + t * kHeadDim + c0) << (BITS * e);
+                }
+            }
+            // byte i of m[b] = byte b of the word of channel c0 + i
+            const uint32_t t01 = __builtin_amdgcn_perm(m[1], m[0], 0x05010400u), u01 = __builtin_amdgcn_perm(m[1], m[0], 0x07030602u);
+            const uint32_t t23 = __builtin_amdgcn_perm(m[3], m[2], 0x05010400u), u23 = __builtin_amdgcn_perm(m[3], m[2], 0x07030602u);
+            const uint32_t wv[4] = {__builtin_amdgcn_perm(t23, t01, 0x05040100u), __builtin_amdgcn_perm(t23, t01, 0x07060302u),
+                                    __builtin_amdgcn_perm(u23, u01, 0x05040100u), __builtin_amdgcn_perm(u23, u01, 0x07060302u)};
+            const int base = (((BITS == 4 ? blk * 2 : 0) + h) * 4 + quad) * 64;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vc[base + (4 * n4 + i) * 4 + k] = wv[i];
+        }
+        return;
+    }
 #pragma unroll
     for (int widx = tid; widx < n_words; widx += 256) {
         const int jl = widx & 3, n = (widx >> 2) & 15, quad = (widx >> 6) & 3, jh = (widx >> 8) & 1;

@@ -3,8 +3,9 @@
 // listed slot, dequantises it into FP16 and writes dense K / V rows in the
 // caller's token order, ready for an FP16 prefill attention kernel.
 //
-// One workgroup of 256 threads owns one (page, kv head) record, the mirror
-// image of the append kernel.  Thread (slot = tid/4, part = tid%4) produces
+// A workgroup of 256 threads handles one (page, kv head) record at a time, the
+// mirror image of the append kernel, and loops over records with the next
+// record's loads already in flight.  Thread (slot = tid/4, part = tid%4) produces
 // channels 32*i + 8*part .. +7 of its token for the four groups i: one
 // 16-byte load fetches its K codes of all four groups, and each of its four
 // 16-byte stores per tensor completes a 64-byte line together with the three
@@ -65,27 +66,96 @@ template <int BITS> __device__ __forceinline__ void spread8(uint32_t w, int shif
          (((v >> (7 * BITS)) & m) << 24);
 }
 
-// KC: the keys of this (INT2) record are quantised per channel over blocks of 32 slots.
+// What one thread requests from HBM for one (page, kv head) record.  The requests of the next record are
+// issued before the current one is processed, so that a compute unit always has loads and stores in flight
+// (workgroups that start together would otherwise all read, then all compute, then all store).
+struct Stage {
+    uint4 kw;         // K codes of this thread's token: its 8 channels of each of the four groups
+    uint2 ksc, kzc;   // K scale / K zero of the token, four groups (per-token keys)
+    uint4 km;         // per-channel keys: 16 bytes of the K scale | K zero planes (threads 0..63)
+    uint4 vw;         // V words of four adjacent channels (threads 0..n_quads-1)
+    uint2 vm;         // 8 bytes of the V scale | V zero planes (threads 0..127)
+    int dst;          // output row of this thread's slot, or -1
+    int page;         // workgroup-uniform; -1 = page id outside the pool, nothing was requested
+    int bm;           // bit_map entry of the page
+};
+static_assert(sizeof(Stage) % 4 == 0, "plain dwords");
+
+// KC: the keys of an INT2 record are quantised per channel over blocks of 32 slots.
 template <int BITS, bool KC>
-__device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, uint16_t *__restrict__ K_out,
-                                              uint16_t *__restrict__ V_out, int dst, bool valid, int head,
-                                              int n_kv_heads, uint8_t (*codes)[kHeadDim], uint16_t *vmeta)
+__device__ __forceinline__ void load_planes(Stage &st, const uint8_t *__restrict__ rec)
 {
     using R = Rec<BITS>;
     const int tid = threadIdx.x, slot = tid >> 2, part = tid & 3;
     const int tile = slot >> 4, row = slot & 15;
-
-    // ---- V planes -> LDS: scale and zero as stored, codes one per byte [token][channel]
-    if (tid < 128) reinterpret_cast<uint2 *>(vmeta)[tid] = reinterpret_cast<const uint2 *>(rec + R::kVScale)[tid];   // 512 B scale, 512 B zero
-    // four words of four adjacent channels at a time, so that a token's four codes go out as one 32-bit write
-    const uint32_t *vc = reinterpret_cast<const uint32_t *>(rec + R::kVCodes);
+    const uint4 *kc = reinterpret_cast<const uint4 *>(rec + R::kKCodes);
+    // INT4: chunk (tile*4 + part)*16 + row = word `part` (8 channels) of the four groups
+    // INT2: chunk (tile*2 + part/2)*16 + row = word part/2 (16 channels); this thread takes half part%2
+    st.kw = BITS == 4 ? kc[(tile * 4 + part) * 16 + row] : kc[(tile * 2 + (part >> 1)) * 16 + row];
+    if constexpr (KC) {
+        if (tid < 64) st.km = reinterpret_cast<const uint4 *>(rec + R::kKScale)[tid];   // 512 B scale, 512 B zero
+    } else {
+        st.ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[slot];
+        st.kzc = reinterpret_cast<const uint2 *>(rec + R::kKZero)[slot];
+    }
+    if (tid < 128) st.vm = reinterpret_cast<const uint2 *>(rec + R::kVScale)[tid];   // 512 B scale, 512 B zero
     constexpr int n_quads = R::kCodeBytes / 16;   // 256 (INT4) / 128 (INT2)
     if (tid < n_quads) {
+        const uint32_t *vc = reinterpret_cast<const uint32_t *>(rec + R::kVCodes);
         const int jl = tid & 3, nq = (tid >> 2) & 3, quad = (tid >> 4) & 3, jh = (tid >> 6) & 1;
         const int blk = tid >> 7;   // INT4 only (0 for INT2)
         const int widx = jl + 16 * nq + 64 * quad + 256 * jh + 512 * blk;   // word of channel c0; c0 + k is 4*k words on
+        st.vw = make_uint4(vc[widx], vc[widx + 4], vc[widx + 8], vc[widx + 12]);
+    }
+}
+
+template <bool KC>
+__device__ __forceinline__ void load_stage(Stage &st, int r, const uint8_t *__restrict__ pool,
+                                           const uint8_t *__restrict__ bit_map, const int32_t *__restrict__ work_pages,
+                                           const int32_t *__restrict__ work_dst, int n_kv_heads, int n_pages_int2,
+                                           int n_pages_int4, int32_t *status)
+{
+    const int w = r / n_kv_heads, head = r % n_kv_heads;
+    const int page = work_pages[w];
+    if (page < 0 || page >= n_pages_int2 + n_pages_int4) {
+        if (status && threadIdx.x == 0) atomicOr(status, TKV_STATUS_PAGE_RANGE);
+        st = Stage{};
+        st.page = -1;
+        return;
+    }
+    st.page = page;
+    st.dst = work_dst[(size_t)w * kPageTokens + (threadIdx.x >> 2)];
+    st.bm = bit_map[page];
+    const uint8_t *rec = pool + record_offset(page, head, n_kv_heads, n_pages_int2);
+    if (page < n_pages_int2) load_planes<2, KC>(st, rec);
+    else load_planes<4, false>(st, rec);
+}
+
+struct GatherLds {
+    alignas(16) uint8_t codes[kPageTokens][kHeadDim];     // V codes, one per byte [token][channel]
+    alignas(16) uint16_t vmeta[2 * kPageTokens * kGroups];   // V scale plane, V zero plane, as stored
+    alignas(16) uint4 kmeta[64];                           // per-channel keys: K scale plane, K zero plane
+};
+
+template <int BITS, bool KC>
+__device__ __forceinline__ void gather_record(const Stage &st, uint16_t *__restrict__ K_out, uint16_t *__restrict__ V_out,
+                                              bool valid, int head, int n_kv_heads, GatherLds &lds)
+{
+    using R = Rec<BITS>;
+    const int tid = threadIdx.x, slot = tid >> 2, part = tid & 3;
+
+    // ---- V planes -> LDS: scale and zero as stored, codes one per byte [token][channel]
+    if (tid < 128) reinterpret_cast<uint2 *>(lds.vmeta)[tid] = st.vm;
+    if constexpr (KC) {
+        if (tid < 64) lds.kmeta[tid] = st.km;
+    }
+    // four words of four adjacent channels at a time, so that a token's four codes go out as one 32-bit write
+    constexpr int n_quads = R::kCodeBytes / 16;
+    if (tid < n_quads) {
+        const int jl = tid & 3, nq = (tid >> 2) & 3, quad = (tid >> 4) & 3, jh = (tid >> 6) & 1;
+        const int blk = tid >> 7;
         const int c0 = (jh * 4 + jl) * 16 + 4 * nq;
-        const uint32_t w0 = vc[widx], w1 = vc[widx + 4], w2 = vc[widx + 8], w3 = vc[widx + 12];
+        const uint32_t w0 = st.vw.x, w1 = st.vw.y, w2 = st.vw.z, w3 = st.vw.w;
         constexpr uint32_t m = (1u << BITS) - 1u;
 #pragma unroll
         for (int p = 0; p < 32 / BITS; ++p) {
@@ -99,23 +169,33 @@ __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, u
             }
             const uint32_t four = ((w0 >> (BITS * p)) & m) | (((w1 >> (BITS * p)) & m) << 8) |
                                   (((w2 >> (BITS * p)) & m) << 16) | (((w3 >> (BITS * p)) & m) << 24);
-            *reinterpret_cast<uint32_t *>(&codes[t][c0]) = four;
+            *reinterpret_cast<uint32_t *>(&lds.codes[t][c0]) = four;
         }
     }
 
-    // ---- K: this thread's 8 channels of each group
-    if (valid) {
-        const uint4 *kc = reinterpret_cast<const uint4 *>(rec + R::kKCodes);
-        // INT4: chunk (tile*4 + part)*16 + row = word `part` (8 channels) of the four groups
-        // INT2: chunk (tile*2 + part/2)*16 + row = word part/2 (16 channels); this thread takes half part%2
-        const uint4 kw = BITS == 4 ? kc[(tile * 4 + part) * 16 + row] : kc[(tile * 2 + (part >> 1)) * 16 + row];
-        const uint32_t w[4] = {kw.x, kw.y, kw.z, kw.w};
-        uint4 *out = reinterpret_cast<uint4 *>(K_out + ((size_t)dst * n_kv_heads + head) * kHeadDim);
-        if constexpr (KC) {
+    // ---- K: this thread's 8 channels of each group (per-token keys need nothing from LDS)
+    const uint32_t w[4] = {st.kw.x, st.kw.y, st.kw.z, st.kw.w};
+    uint4 *kout = reinterpret_cast<uint4 *>(K_out + ((size_t)st.dst * n_kv_heads + head) * kHeadDim);
+    if constexpr (!KC) {
+        if (valid) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t sc = i < 2 ? st.ksc.x : st.ksc.y, zc = i < 2 ? st.kzc.x : st.kzc.y;
+                const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc >> (16 * (i & 1))));
+                const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(zc >> (16 * (i & 1))));
+                uint32_t lo, hi;
+                spread8<BITS>(w[i], BITS == 4 ? 0 : 16 * (part & 1), lo, hi);
+                kout[4 * i + part] = dequant8(lo, hi, s, z);
+            }
+        }
+    }
+    __syncthreads();
+    if constexpr (KC) {
+        if (valid) {
             // channels 32*i + 8*part + j: chunks (block, group i, quarter 2*(part/2) + j/4) of the planes, fp16
-            // half part%2 of word j%4.  Each plane is 1 KiB per record and stays in cache.
-            const uint4 *sp4 = reinterpret_cast<const uint4 *>(rec + R::kKScale) + (slot >> 5) * 16 + 2 * (part >> 1);
-            const uint4 *zp4 = reinterpret_cast<const uint4 *>(rec + R::kKZero) + (slot >> 5) * 16 + 2 * (part >> 1);
+            // half part%2 of word j%4
+            const uint4 *sp4 = lds.kmeta + (slot >> 5) * 16 + 2 * (part >> 1);
+            const uint4 *zp4 = sp4 + 32;
             const uint32_t sel = (part & 1) ? 0x07060302u : 0x05040100u;   // v_perm: the chosen halves of (second, first)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -126,63 +206,58 @@ __device__ __forceinline__ void gather_record(const uint8_t *__restrict__ rec, u
                                         __builtin_amdgcn_perm(z1.y, z1.x, sel), __builtin_amdgcn_perm(z1.w, z1.z, sel)};
                 uint32_t lo, hi;
                 spread8<BITS>(w[i], 16 * (part & 1), lo, hi);
-                out[4 * i + part] = dequant8_each(lo, hi, sp, zp);
+                kout[4 * i + part] = dequant8_each(lo, hi, sp, zp);
             }
-        } else {
-        const uint2 ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[slot];
-        const uint2 kzc = reinterpret_cast<const uint2 *>(rec + R::kKZero)[slot];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t sc = i < 2 ? ksc.x : ksc.y, zc = i < 2 ? kzc.x : kzc.y;
-            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc >> (16 * (i & 1))));
-            const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(zc >> (16 * (i & 1))));
-            uint32_t lo, hi;
-            spread8<BITS>(w[i], BITS == 4 ? 0 : 16 * (part & 1), lo, hi);
-            out[4 * i + part] = dequant8(lo, hi, s, z);
-        }
         }
     }
-    __syncthreads();
     // ---- V: codes from the byte tile, scale / zero from the staged planes
     if (valid) {
-        uint4 *out = reinterpret_cast<uint4 *>(V_out + ((size_t)dst * n_kv_heads + head) * kHeadDim);
+        uint4 *out = reinterpret_cast<uint4 *>(V_out + ((size_t)st.dst * n_kv_heads + head) * kHeadDim);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int mi = vmeta_index(slot, i);
-            const _Float16 s = __builtin_bit_cast(_Float16, vmeta[mi]);
-            const _Float16 z = __builtin_bit_cast(_Float16, vmeta[kPageTokens * kGroups + mi]);
-            const uint2 cb = *reinterpret_cast<const uint2 *>(&codes[slot][32 * i + 8 * part]);
+            const _Float16 s = __builtin_bit_cast(_Float16, lds.vmeta[mi]);
+            const _Float16 z = __builtin_bit_cast(_Float16, lds.vmeta[kPageTokens * kGroups + mi]);
+            const uint2 cb = *reinterpret_cast<const uint2 *>(&lds.codes[slot][32 * i + 8 * part]);
             out[4 * i + part] = dequant8(cb.x, cb.y, s, z);
         }
     }
 }
 
+// Workgroup b handles records b, b + gridDim.x, ... (record = work page * n_kv_heads + head).  The LDS tile is
+// double-buffered: one barrier per record (a thread can be at most one record ahead of the slowest).
 template <bool KC>
 __global__ __launch_bounds__(256) void tkv_gather_kernel(
     const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map, const int32_t *__restrict__ work_pages,
-    const int32_t *__restrict__ work_dst, int n_kv_heads, int n_pages_int2, int n_pages_int4,
+    const int32_t *__restrict__ work_dst, int n_records, int n_kv_heads, int n_pages_int2, int n_pages_int4,
     uint16_t *__restrict__ K_out, uint16_t *__restrict__ V_out, int n_tokens, int32_t *status)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t codes[kPageTokens][kHeadDim];
-    __shared__ __attribute__((aligned(16))) uint16_t vmeta[2 * kPageTokens * kGroups];
-    const int w = blockIdx.x / n_kv_heads, head = blockIdx.x % n_kv_heads;
-    const int page = work_pages[w];
-    if (page < 0 || page >= n_pages_int2 + n_pages_int4) {
-        if (status && threadIdx.x == 0) atomicOr(status, TKV_STATUS_PAGE_RANGE);
-        return;
+    __shared__ GatherLds lds[2];
+    int r = blockIdx.x;
+    if (r >= n_records) return;
+    Stage cur{}, nxt{};
+    load_stage<KC>(cur, r, pool, bit_map, work_pages, work_dst, n_kv_heads, n_pages_int2, n_pages_int4, status);
+    nxt = cur;
+    int buf = 0;
+    for (; r < n_records; r += gridDim.x) {
+        const int rn = r + gridDim.x;
+        if (rn < n_records)
+            load_stage<KC>(nxt, rn, pool, bit_map, work_pages, work_dst, n_kv_heads, n_pages_int2, n_pages_int4, status);
+        if (cur.page >= 0) {
+            const int bits = cur.page < n_pages_int2 ? 2 : 4;
+            // a page that was never written, or written at another width, has been read (its address is valid)
+            // and nothing of it is stored
+            const bool written = cur.bm == bits;
+            if (!written && status && threadIdx.x == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
+            const bool valid = written && cur.dst >= 0 && cur.dst < n_tokens;
+            if (written && cur.dst >= n_tokens && status && (threadIdx.x & 3) == 0) atomicOr(status, TKV_STATUS_DST_RANGE);
+            const int head = r % n_kv_heads;
+            if (bits == 2) gather_record<2, KC>(cur, K_out, V_out, valid, head, n_kv_heads, lds[buf]);
+            else gather_record<4, false>(cur, K_out, V_out, valid, head, n_kv_heads, lds[buf]);
+            buf ^= 1;
+        }
+        cur = nxt;
     }
-    const int bits = page < n_pages_int2 ? 2 : 4;
-    if (bit_map[page] != bits) {   // never written, or written at another width: nothing to read
-        if (status && threadIdx.x == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
-        return;
-    }
-    const int slot = threadIdx.x >> 2;
-    const int dst = work_dst[(size_t)w * kPageTokens + slot];
-    const bool valid = dst >= 0 && dst < n_tokens;
-    if (dst >= n_tokens && status && (threadIdx.x & 3) == 0) atomicOr(status, TKV_STATUS_DST_RANGE);
-    const uint8_t *rec = pool + record_offset(page, head, n_kv_heads, n_pages_int2);
-    if (bits == 2) gather_record<2, KC>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
-    else gather_record<4, false>(rec, K_out, V_out, dst, valid, head, n_kv_heads, codes, vmeta);
 }
 
 } // namespace
@@ -191,10 +266,24 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
                       const int32_t *work_dst, int32_t n_work, void *K_out, void *V_out, int32_t n_tokens,
                       int32_t *status, void *stream)
 {
-    const dim3 grid((unsigned)(n_work * desc->n_kv_heads)), block(256);
-    auto kernel = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL ? tkv_gather_kernel<true> : tkv_gather_kernel<false>;
+    // A few looping workgroups per compute unit, fewer than would fit: the kernel is bound by the HBM write
+    // stream (82 % of its bytes are stores), and on MI355X that stream runs faster with fewer concurrent
+    // writers (cfg2, per-token keys: 339 / 283 / 298 / 316 / 344 us with 1 / 2 / 3 / 4 / 7 workgroups per
+    // unit; per-channel keys, which do more work per record: 448 / 371 / 328 / 330 / 346 with 1 .. 5).
+    const bool kc = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL;
+    auto kernel = kc ? tkv_gather_kernel<true> : tkv_gather_kernel<false>;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu <= 0)
+        return TKV_ERR_HIP;
+    const int wanted = kc ? 3 : 2;
+    per_cu = per_cu < wanted ? per_cu : wanted;
+    const int n_records = n_work * desc->n_kv_heads;
+    const int n_blocks = n_records < cus * per_cu ? n_records : cus * per_cu;
+    const dim3 grid((unsigned)n_blocks), block(256);
     hipLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)stream, (const uint8_t *)pool, bit_map,
-                       work_pages, work_dst, desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4,
+                       work_pages, work_dst, n_records, desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4,
                        (uint16_t *)K_out, (uint16_t *)V_out, n_tokens, status);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
 }
