@@ -317,8 +317,13 @@ int tkv_launch_append(const tkv_desc *desc, void *pool, uint8_t *bit_map, const 
                       const int32_t *work_src, int32_t n_work, int32_t *status, void *stream)
 {
     const dim3 grid((unsigned)(n_work * desc->n_kv_heads)), block(256);
-    auto kernel = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL ? tkv_append_kernel<true> : tkv_append_kernel<false>;
-    hipLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)stream, (uint8_t *)pool, bit_map,
+    const bool kc = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL;
+    auto kernel = kc ? tkv_append_kernel<true> : tkv_append_kernel<false>;
+    // The kernel is bound by the memory system, which serves four resident workgroups per compute unit
+    // slightly faster than the eight that would fit (cfg2: 282 vs 294 us; 3 -> 282, 2 -> 339, 6 -> 286): unused
+    // dynamic LDS holds the residency at four.  The per-channel-key kernel's own 33 KB do the same.
+    const size_t pad_lds = kc ? 0 : 24 * 1024;
+    hipLaunchKernelGGL(kernel, grid, block, pad_lds, (hipStream_t)stream, (uint8_t *)pool, bit_map,
                        (const uint16_t *)K, (const uint16_t *)V, tag_bits, n_tokens, work_pages, work_src,
                        desc->n_kv_heads, desc->n_pages_int2, desc->n_pages_int4, status);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
