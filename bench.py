@@ -163,6 +163,9 @@ def main():
     split_per, _ = time_steps(split_cold, args.steps, args.warmup)
     ev_ms = float(np.mean(split_per))
     warm_per, _ = time_steps(step_warm, min(args.steps, 50), 5)
+    # speed-of-light probe: a plain 128-bit streaming read of the same pool copies, same rotation
+    probe_per, _ = time_steps(lambda i: tkv.tkv_probe_stream_read(pools[i % n_copies]), 40, 5)
+    stream_read = pool_bytes / (float(np.mean(probe_per)) * 1e-3) / 1e9
     assert int(cache.status.item()) == 0
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -194,9 +197,12 @@ def main():
                      "frac": kv_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": read_traffic("decode_%s_hbm_traffic.txt" % args.config),
                      "kernel": "tkv_decode_kernel", "kernel_us": ev_ms * 1e3,
+                     "stream_read_GBps": stream_read, "frac_of_stream_read": kv_bytes / (ev_ms * 1e-3) / 1e9 / stream_read,
                      "note": "tkv_decode_kernel launched by itself (tkv_decode_split), mean of HIP-event intervals "
                              "between back-to-back launches; algorithmic bytes = 96 B/INT2 token + 160 B/INT4 token "
-                             "per kv head; traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE"},
+                             "per kv head; traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE; "
+                             "stream_read_GBps = a plain 128-bit streaming read of the same pool copies (tkv_probe_stream_read), "
+                             "what the memory system delivers to a read-only scan on this box"},
     }
     # ---- the same workload with the paper's own INT2 key scheme (keys per channel over 32-token blocks,
     #      tokens that do not fill a block stored at INT4): append, gather and decode legs

@@ -357,6 +357,21 @@ int tkv_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int3
                       int32_t batch, int32_t n_q_heads, float *out, const void *workspace,
                       size_t workspace_bytes, void *stream /* hipStream_t */);
 
+/* ------------------------------------------------------------------ */
+/* Measurement aid (device).                                            */
+/* ------------------------------------------------------------------ */
+/*
+ * Streams `bytes` (a multiple of 16) of the device buffer `buf` (16-byte
+ * aligned) through the GPU with 128-bit loads and discards them: the
+ * read-bandwidth ceiling of the device for a scan such as the decode kernel's
+ * pass over the pool.  For benchmarks that report a kernel against what the
+ * memory system delivers as well as against the published peak; it computes
+ * nothing of the method.  `sink` (device u32, may be NULL) is never written
+ * in practice.  One launch on `stream`; TKV_ERR_INVALID_ARG on a null or
+ * misaligned buffer.
+ */
+int tkv_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *stream /* hipStream_t */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtkv.so")
-SOURCES = ["tkv_host.cpp", "tkv_append.hip", "tkv_gather.hip", "tkv_decode.hip"]
+SOURCES = ["tkv_host.cpp", "tkv_append.hip", "tkv_gather.hip", "tkv_decode.hip", "tkv_probe.hip"]
 
 
 def build(verbose: bool = False) -> str:

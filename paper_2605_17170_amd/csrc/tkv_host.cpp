@@ -421,6 +421,13 @@ int tkv_tag_counts(const uint8_t *tags, int32_t n_tokens, int64_t *counts)
     return TKV_OK;
 }
 
+int tkv_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (bytes == 0) return TKV_OK;
+    if (!buf || ((uintptr_t)buf & 15) || (bytes & 15)) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_probe_read(buf, bytes, sink, stream);
+}
+
 namespace {
 int alloc_args_status(int32_t n_tags, const int64_t *N, const double *D2, const double *D4, double B, const uint8_t *out)
 {

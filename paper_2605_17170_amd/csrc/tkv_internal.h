@@ -14,6 +14,8 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
                       const int32_t *work_dst, int32_t n_work, void *K_out, void *V_out, int32_t n_tokens,
                       int32_t *status, void *stream);
 
+int tkv_launch_probe_read(const void *buf, size_t bytes, uint32_t *sink, void *stream);
+
 int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
                             const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,
                             const int32_t *n_tok_int4, const int32_t *items, int32_t n_items, int32_t batch,

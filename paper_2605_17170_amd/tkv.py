@@ -41,7 +41,7 @@ EXPORTS = [
     "tkv_seq_page_ids", "tkv_route_residual", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
     "tkv_decode_split", "tkv_decode_reduce", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
-    "tkv_tag_tokens", "tkv_tags_to_bits", "tkv_tag_counts",
+    "tkv_tag_tokens", "tkv_tags_to_bits", "tkv_tag_counts", "tkv_probe_stream_read",
 ]
 
 
@@ -119,6 +119,7 @@ def lib():
                                            vp, vp, sz, vp, vp]
         L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
         L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.tkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
         L.tkv_tag_tokens.argtypes = [vp, vp, i32, vp]
         L.tkv_tags_to_bits.argtypes = [vp, i32, vp, vp]
         L.tkv_tag_counts.argtypes = [vp, i32, vp]
@@ -420,3 +421,11 @@ def tkv_tag_counts(tags) -> np.ndarray:
     counts = np.zeros(N_TAGS, np.int64)
     _check(lib().tkv_tag_counts(pt, tg.size, C.c_void_p(counts.ctypes.data)), "tkv_tag_counts")
     return counts
+
+
+# ---------------------------------------------------------------- measurement aid (device)
+def tkv_probe_stream_read(buf, stream=None):
+    """Plain 128-bit streaming read of a torch device tensor (read-bandwidth ceiling for benchmarks)."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().tkv_probe_stream_read(_dev(buf), nbytes - nbytes % 16, C.c_void_p(None), _stream(stream)),
+           "tkv_probe_stream_read")

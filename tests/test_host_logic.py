@@ -309,3 +309,11 @@ def test_per_channel_key_mode_is_validated():
     assert items.tolist() == [[0, 0, 1, 0]]
     tkv.tkv_seq_destroy(s)
     tkv.tkv_alloc_destroy(a)
+
+
+def test_stream_read_probe_validates_before_launch():
+    L = tkv.lib()
+    assert L.tkv_probe_stream_read(None, 0, None, None) == tkv.TKV_OK                 # nothing to read
+    assert L.tkv_probe_stream_read(None, 64, None, None) == tkv.TKV_ERR_INVALID_ARG
+    assert L.tkv_probe_stream_read(C.c_void_p(0x1008), 64, None, None) == tkv.TKV_ERR_INVALID_ARG   # misaligned
+    assert L.tkv_probe_stream_read(C.c_void_p(0x1000), 24, None, None) == tkv.TKV_ERR_INVALID_ARG   # not a multiple of 16
