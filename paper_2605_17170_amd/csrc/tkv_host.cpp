@@ -1,11 +1,14 @@
 // Host side of libtkv: geometry, the two page allocators, per-sequence page
-// tables, the append and decode planners, and argument validation in front of
-// the kernel launchers.  Nothing here touches the GPU; the launchers live in
-// tkv_append.hip and tkv_decode.hip.
+// tables, the append and decode planners, the residual routing of per-channel
+// INT2 keys, the triaxial tagger and the tag -> bitwidth allocation, and
+// argument validation in front of the kernel launchers.  Nothing here touches
+// the GPU; the launchers live in tkv_append.hip, tkv_gather.hip,
+// tkv_decode.hip and tkv_probe.hip.
 //
 // Paper passages: offset-split shared address space and one allocator per
 // pool, Sec. 3.2.2; per-token bitwidth array routing tokens to the pools and
-// the INT2-first partition of the page table, Sec. 3.2.3.
+// the INT2-first partition of the page table, Sec. 3.2.3; residual policy,
+// Sec. 3.2.1; tag space, Sec. 3.1; budgeted allocation, Sec. 3.1.3.
 #include "tkv.h"
 #include "tkv_internal.h"
 

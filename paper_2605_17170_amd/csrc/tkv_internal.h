@@ -1,5 +1,6 @@
 // Internal interface between the host-side validation (tkv_host.cpp) and the
-// kernel launchers (tkv_append.hip, tkv_decode.hip).  Arguments are already
+// kernel launchers (tkv_append.hip, tkv_gather.hip, tkv_decode.hip,
+// tkv_probe.hip).  Arguments are already
 // validated; the launchers return TKV_OK or TKV_ERR_HIP.
 #ifndef TKV_INTERNAL_H
 #define TKV_INTERNAL_H
