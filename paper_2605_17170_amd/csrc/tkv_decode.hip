@@ -705,20 +705,24 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
 }
 
 // D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence.
-// One workgroup per (sequence, query head): the items' maxima are reduced in parallel, the weights go
-// to LDS, then four groups of 128 threads (one thread per channel) each sum every fourth item.
-constexpr int kReduceParts = 4;
-__global__ __launch_bounds__(kHeadDim * kReduceParts) void tkv_reduce_kernel(
+// One workgroup of 512 threads per (sequence, query head, slice of CH channels): the items' maxima are reduced in
+// parallel, the weights go to LDS, then 512 / CH groups of CH threads (one thread per channel) each sum every
+// (512 / CH)-th item.  CH = 128 (four groups) when a sequence has tens of items; CH = 16 (32 groups, eight
+// workgroups per head) when it has hundreds, as a single long sequence with one kv head does.
+constexpr int kReduceThreads = 512;
+template <int CH>
+__global__ __launch_bounds__(kReduceThreads) void tkv_reduce_kernel(
     const float *__restrict__ acc_ws, const float *__restrict__ ml_ws, const int32_t *__restrict__ seq_item_indptr,
     int n_q_heads, float *__restrict__ out)
 {
-    constexpr int kThreads = kHeadDim * kReduceParts, kChunk = 512;
+    constexpr int kThreads = kReduceThreads, kChunk = 512, kParts = kThreads / CH, kSlices = kHeadDim / CH;
     __shared__ float w_s[kChunk];
     __shared__ float red[kThreads / 64];
-    __shared__ float part_s[kReduceParts][kHeadDim];
-    __shared__ float den_s[kReduceParts];
-    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, tid = threadIdx.x;
-    const int c = tid % kHeadDim, part = tid / kHeadDim;
+    __shared__ float part_s[kParts][CH];
+    __shared__ float den_s[kParts];
+    const int bh = blockIdx.x / kSlices, slice = blockIdx.x % kSlices;
+    const int b = bh / n_q_heads, h = bh % n_q_heads, tid = threadIdx.x;
+    const int cl = tid % CH, c = slice * CH + cl, part = tid / CH;
     const int i0 = seq_item_indptr[b], i1 = seq_item_indptr[b + 1];
     // global maximum of the items' reference maxima
     float M = -INFINITY;
@@ -737,20 +741,20 @@ __global__ __launch_bounds__(kHeadDim * kReduceParts) void tkv_reduce_kernel(
             if (tid < n) w_s[tid] = __builtin_amdgcn_exp2f(ml_ws[2 * ((size_t)(base + tid) * n_q_heads + h)] - M);
             __syncthreads();
 #pragma unroll 4
-            for (int k = part; k < n; k += kReduceParts) {
+            for (int k = part; k < n; k += kParts) {
                 const size_t ph = (size_t)(base + k) * n_q_heads + h;
                 num = fmaf(w_s[k], acc_ws[ph * kHeadDim + c], num);
-                if (c == 0) den = fmaf(w_s[k], ml_ws[2 * ph + 1], den);
+                if (cl == 0) den = fmaf(w_s[k], ml_ws[2 * ph + 1], den);
             }
         }
     }
-    part_s[part][c] = num;
-    if (c == 0) den_s[part] = den;
+    part_s[part][cl] = num;
+    if (cl == 0) den_s[part] = den;
     __syncthreads();
     if (part == 0) {
         float nsum = 0.0f, dsum = 0.0f;
 #pragma unroll
-        for (int k = 0; k < kReduceParts; ++k) { nsum += part_s[k][c]; dsum += den_s[k]; }
+        for (int k = 0; k < kParts; ++k) { nsum += part_s[k][cl]; dsum += den_s[k]; }
         out[((size_t)b * n_q_heads + h) * kHeadDim + c] = dsum > 0.0f ? nsum / dsum : 0.0f;
     }
 }
@@ -781,7 +785,12 @@ int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indpt
     (void)desc;
     const float *acc_ws = (const float *)workspace;
     const float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
-    hipLaunchKernelGGL(tkv_reduce_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kHeadDim * kReduceParts), 0,
-                       (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
+    // the item counts are on the device; the average per sequence picks the shape of the reduction
+    if ((int64_t)n_items > 128 * (int64_t)batch)
+        hipLaunchKernelGGL(tkv_reduce_kernel<16>, dim3((unsigned)(batch * n_q_heads * (kHeadDim / 16))), dim3(kReduceThreads), 0,
+                           (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
+    else
+        hipLaunchKernelGGL(tkv_reduce_kernel<128>, dim3((unsigned)(batch * n_q_heads)), dim3(kReduceThreads), 0,
+                           (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
 }

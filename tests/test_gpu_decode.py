@@ -105,6 +105,22 @@ def test_split_count_and_page_scatter_invariance(G):
         assert np.allclose(o, outs[0], rtol=1e-3, atol=2e-4)
 
 
+def test_hundreds_of_items_per_sequence(G):
+    """One long sequence on one kv head cut into one item per page: the cross-split reduction then runs in its
+    wide shape (channel slices, 32 item groups per slice); same result as with few items."""
+    q, K, V, seq_bits = G.random_case(27, [12800], 4, 1)
+    cache, (Kq, Vq) = G.check_append(seq_bits, K, V, 1)
+    try:
+        ref = G.decode_ref(q, Kq, Vq, [12800])
+        for target in (1000, 3):
+            out = G.gpu_decode(cache, q, target)
+            n_items = cache._plan[2].shape[0]
+            assert (n_items > 128) == (target == 1000)
+            G.assert_close(out, ref, "target_items=%d (%d items)" % (target, n_items))
+    finally:
+        cache.close()
+
+
 def test_decode_on_oracle_packed_pool(G):
     """Isolates decode from append: the pool bytes come from the oracle's codec."""
     q, K, V, seq_bits = G.random_case(18, [700, 90], 8, 2)
