@@ -129,3 +129,25 @@ def test_cfg4_full_size(G):
     cache, _ = G.check_append(w.bits, K, V, w.n_kv_heads, pool_factor=1.25)
     assert cache.work_pages.size == 1024
     cache.close()
+
+
+@pytest.mark.parametrize("axis", [tkv.TKV_KEYS_PER_TOKEN, tkv.TKV_KEYS_PER_CHANNEL])
+def test_random_bf16_bit_patterns(G, axis):
+    """Values drawn as raw bf16 bit patterns (every finite exponent up to 2^15, both signs, subnormals, +-0) mixed
+    with narrow-range groups: ties, clamping on both sides, scales that overflow to the top of fp16 or flush to 0."""
+    rng = np.random.default_rng(41)
+    T, H = 2048, 4
+    def draw():
+        b = rng.integers(0, 1 << 16, (T, H, 128), dtype=np.uint16)
+        exp = (b >> 7) & 0xff
+        b = np.where(exp > 141, (b & 0x807f) | (np.uint16(141) << 7), b).astype(np.uint16)   # |x| < 2^15
+        narrow = rng.random((T, H, 4, 1)) < 0.5                                              # half of the groups: one binade
+        base = rng.integers(100, 140, (T, H, 4, 1)).astype(np.uint16)
+        nb = ((b.reshape(T, H, 4, 32) & 0x807f) | (base << 7)).astype(np.uint16)
+        return np.where(narrow, nb, b.reshape(T, H, 4, 32)).reshape(T, H, 128).astype(np.uint16)
+    K, V = draw(), draw()
+    bits = rng.choice([2, 4], T).astype(np.uint8)
+    if axis == tkv.TKV_KEYS_PER_CHANNEL:
+        G.kc_check_append([bits], K, V, H)[0].close()
+    else:
+        G.check_append([bits], K, V, H)[0].close()
