@@ -121,6 +121,27 @@ def test_hundreds_of_items_per_sequence(G):
         cache.close()
 
 
+def test_workspace_and_output_are_written_inside_their_bounds(G):
+    """Guard words behind the workspace (sized by tkv_decode_workspace_bytes) and around `out` keep their canary."""
+    q, K, V, seq_bits = G.random_case(28, [700, 130], 8, 2)
+    cache, (Kq, Vq) = G.check_append(seq_bits, K, V, 2)
+    try:
+        items, _ = cache.plan_decode(9)
+        need = tkv.tkv_decode_workspace_bytes(cache.desc, items.shape[0], 8)
+        guard = 4096
+        ws = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device=G.DEV)
+        obuf = torch.full((guard + 2 * 8 * 128 * 4 + guard,), 0x5A, dtype=torch.uint8, device=G.DEV)
+        out = obuf[guard:guard + 2 * 8 * 128 * 4].view(torch.float32).view(2, 8, 128)
+        cache.decode(harness.bf16_tensor(q, G.DEV), out=out, workspace=ws[:need])
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == 0
+        assert bool((ws[need:] == 0x5A).all()), "write behind the workspace"
+        assert bool((obuf[:guard] == 0x5A).all()) and bool((obuf[-guard:] == 0x5A).all()), "write outside out"
+        G.assert_close(out.cpu().numpy(), G.decode_ref(q, Kq, Vq, [700, 130]), "guarded buffers")
+    finally:
+        cache.close()
+
+
 def test_decode_on_oracle_packed_pool(G):
     """Isolates decode from append: the pool bytes come from the oracle's codec."""
     q, K, V, seq_bits = G.random_case(18, [700, 90], 8, 2)
