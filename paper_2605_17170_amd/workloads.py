@@ -176,13 +176,11 @@ def agentic_trace(rng: np.random.Generator, ctx: int, image_share: float,
 
 
 def bits_table(tag_counts: np.ndarray, rng: np.random.Generator, f4_target: float) -> np.ndarray:
-    """Tag -> bitwidth table for a synthetic workload.  Per-tag sensitivities
-    are seeded random numbers (no calibration data exists here); tags are
-    upgraded from 2 to 4 bits in decreasing order of per-bit gain while the
-    extra 2*N_k bits fit the budget B = 2 + 2*f4_target (the greedy walk of
-    Sec. 3.1.3 / Algorithm 1).  `current` and `inst` tags are given the
-    largest gains and image tags zero gain, as the paper's allocations keep
-    recent and instruction tokens at INT4 and route screenshots to INT2."""
+    """Tag -> bitwidth table of a synthetic workload: an INPUT recipe, not the allocator under test (no
+    calibration data exists here, so there are no distortions to allocate by).  Tags get a seeded random
+    priority and are set to 4 bits in priority order while their tokens still fit an INT4 token share of
+    f4_target; `current` and `inst` tags come first and image tags never, as the paper's allocations keep
+    recent and instruction tokens at INT4 and route screenshots to INT2 (Appendix B)."""
     n = tag_counts.astype(np.float64)
     temporal, modal, semantic = tag_fields(np.arange(N_TAGS))
     gain = rng.lognormal(0.0, 1.0, N_TAGS)
