@@ -170,7 +170,7 @@ def main():
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
 
     res = {
-        "metric": "effective KV GB/s, decode attention over mixed INT2/INT4 paged cache (one layer)",
+        "metric": "effective KV GB/s + \u00b5s/decode step (mixed INT2/INT4), % of HBM peak",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "us_per_decode_step": ms_per_step * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u2/u4 codes, f16 MFMA operands, f32 accumulate",
