@@ -187,11 +187,11 @@ __device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head
                 c1 = c0 + 4;
                 f = (k & 1) ? 0.0625f : 1.0f;
             } else {
-                // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 4^k of the 16-channel word q4/2
+                // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^(2k+3) of the 16-channel word q4/2
                 c0 = 32 * g + 16 * (q4 >> 1) + 4 * (q4 & 1) + k;
                 c1 = c0 + 8;
-                // per-channel keys: the unpack leaves the fields three bits higher (see compute_page)
-                f = 1.0f / (float)(1 << (2 * k + (KC ? 3 : 0)));
+                // the unpack leaves the field of slot k at bit 2k + 3 (see compute_page)
+                f = 1.0f / (float)(1 << (2 * k + 3));
             }
             r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
             if constexpr (KC && BITS == 2) rp[k] = pack_h2((float)qf[c0], (float)qf[c1]);
@@ -353,8 +353,11 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
                 const uint32_t w8 = w[g] >> 8;
                 a = as_half8(w[g] & 0x000f000fu, w[g] & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u);
             } else {
-                const uint32_t ws = w[g] >> (8 * (q4 & 1));
-                a = as_half8(ws & 0x00030003u, ws & 0x000c000cu, ws & 0x00300030u, ws & 0x00c000c0u);
+                // this lane's 16 codes of the word are its upper or lower half; the rotate leaves the fields at bits
+                // 4:3, 6:5, 8:7, 10:9 of each half (towards the top of the fp16 mantissa, as for V: the matrix core
+                // drops product bits below its alignment window), stray bits fall outside the masks
+                const uint32_t ws = __builtin_amdgcn_alignbit(w[g], w[g], (q4 & 1) ? 5u : 29u);
+                a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
             }
             const uint4 qb = lds.qo[g][lane];
             const half8 b = as_half8(qb.x, qb.y, qb.z, qb.w);
