@@ -357,6 +357,29 @@ int tkv_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int3
                       int32_t batch, int32_t n_q_heads, float *out, const void *workspace,
                       size_t workspace_bytes, void *stream /* hipStream_t */);
 
+/*
+ * tkv_decode_attention for callers that cannot allocate device memory or pass
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same checks, same two launches and
+ * the same results; the partials live in a fixed device array inside the
+ * library (TKV_DECODE_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends) instead of a caller workspace.  The call allocates and frees nothing.
+ * TKV_ERR_WORKSPACE_TOO_SMALL when tkv_decode_workspace_bytes(desc, n_items,
+ * n_q_heads) exceeds the array (nothing is launched); TKV_ERR_HIP when the
+ * array's address cannot be obtained.  The device that owns `stream` must be
+ * the current device.  All calls on one GPU share the array: two calls whose
+ * kernels may overlap in time (different streams, or replays of captured
+ * graphs running concurrently) race on it; calls on one stream are ordered
+ * and safe.
+ */
+#define TKV_DECODE_STATIC_SCRATCH_BYTES (16u << 20)
+int tkv_decode_attention_static(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                                const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                                const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                                const int32_t *items, const int32_t *seq_item_indptr, int32_t n_items,
+                                int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
+                                int32_t *status, void *stream /* hipStream_t */);
+
 /* ------------------------------------------------------------------ */
 /* Measurement aid (device).                                            */
 /* ------------------------------------------------------------------ */

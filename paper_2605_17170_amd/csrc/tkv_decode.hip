@@ -36,6 +36,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "tkv_internal.h"
@@ -796,4 +797,60 @@ int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indpt
         hipLaunchKernelGGL(tkv_reduce_kernel<128>, dim3((unsigned)(batch * n_q_heads)), dim3(kReduceThreads), 0,
                            (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
+}
+
+// ---- tkv_decode_attention_static: the same two launches with the partials in a file-scope device array ----
+// For callers that cannot allocate (HIP graph capture, tight serving loops).  `scratch` is a host-side
+// stand-in for the device array: its device address is looked up once per device and only that address
+// is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[TKV_DECODE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, null until first use there
+
+// Device address of this device's copy of `scratch` (the current device), or null on failure.
+void *scratch_address()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+} // namespace
+
+extern "C" int tkv_decode_attention_static(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
+                                           const void *q, const int32_t *page_indptr, const int32_t *page_ids,
+                                           const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                                           const int32_t *items, const int32_t *seq_item_indptr, int32_t n_items,
+                                           int32_t batch, int32_t n_q_heads, float sm_scale, float *out,
+                                           int32_t *status, void *stream)
+{
+    // the argument checks of tkv_decode_attention, with the fixed array as the workspace
+    const size_t need = tkv_decode_workspace_bytes(desc, n_items, n_q_heads);
+    if (desc && n_items > 0 && n_q_heads > 0 && need == 0) return TKV_ERR_BAD_SHAPE;
+    if (need > (size_t)TKV_DECODE_STATIC_SCRATCH_BYTES) return TKV_ERR_WORKSPACE_TOO_SMALL;
+    alignas(16) static const char placeholder[16] = {0};   // stands for the workspace in the host-side checks (non-null, aligned)
+    if (int st = tkv_decode_check_args(desc, n_items, batch, n_q_heads, placeholder, TKV_DECODE_STATIC_SCRATCH_BYTES)) return st;
+    if (batch == 0) return TKV_OK;
+    if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
+    if (!q || !out || !page_indptr || !n_tok_int2 || !n_tok_int4 || !seq_item_indptr) return TKV_ERR_INVALID_ARG;
+    if (n_items > 0 && (!pool || !bit_map || !page_ids || !items)) return TKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool & 255) || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return TKV_ERR_INVALID_ARG;
+    void *ws = scratch_address();
+    if (!ws) return TKV_ERR_HIP;
+    // every partial the reduction reads is written by the split kernel of this call: nothing to clear
+    if (int st = tkv_launch_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                                         n_items, batch, n_q_heads, sm_scale, ws, status, stream))
+        return st;
+    return tkv_launch_decode_reduce(desc, seq_item_indptr, n_items, batch, n_q_heads, out, ws, stream);
 }

@@ -527,10 +527,11 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
     return (size_t)n_items * (size_t)n_q_heads * (size_t)(desc->head_dim + 2) * sizeof(float);
 }
 
-namespace {
-// Checks shared by the three decode entry points.  `need_pool` / `need_out` select the arguments a call uses.
-int decode_args_status(const tkv_desc *desc, int32_t n_items, int32_t batch, int32_t n_q_heads,
-                       const void *workspace, size_t workspace_bytes)
+} // extern "C"
+
+// Checks shared by the decode entry points.
+int tkv_decode_check_args(const tkv_desc *desc, int32_t n_items, int32_t batch, int32_t n_q_heads,
+                          const void *workspace, size_t workspace_bytes)
 {
     if (int st = desc_status(desc)) return st;
     if (batch < 0 || n_items < 0 || n_q_heads <= 0) return TKV_ERR_INVALID_ARG;
@@ -543,7 +544,8 @@ int decode_args_status(const tkv_desc *desc, int32_t n_items, int32_t batch, int
     if ((int64_t)n_items * desc->n_kv_heads > INT32_MAX || (int64_t)batch * n_q_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
     return TKV_OK;
 }
-} // namespace
+
+extern "C" {
 
 int tkv_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map,
                      const void *q, const int32_t *page_indptr, const int32_t *page_ids,
@@ -551,7 +553,7 @@ int tkv_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_
                      const int32_t *items, int32_t n_items, int32_t batch, int32_t n_q_heads,
                      float sm_scale, void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
 {
-    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
+    if (int st = tkv_decode_check_args(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
     if (batch == 0 || n_items == 0) return TKV_OK;
     if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
     if (!q || !page_indptr || !n_tok_int2 || !n_tok_int4 || !pool || !bit_map || !page_ids || !items) return TKV_ERR_INVALID_ARG;
@@ -564,7 +566,7 @@ int tkv_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int3
                       int32_t batch, int32_t n_q_heads, float *out, const void *workspace,
                       size_t workspace_bytes, void *stream)
 {
-    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
+    if (int st = tkv_decode_check_args(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
     if (batch == 0) return TKV_OK;
     if (!out || !seq_item_indptr || ((uintptr_t)out & 15)) return TKV_ERR_INVALID_ARG;
     return tkv_launch_decode_reduce(desc, seq_item_indptr, n_items, batch, n_q_heads, out, workspace, stream);
@@ -578,7 +580,7 @@ int tkv_decode_attention(const tkv_desc *desc, const void *pool, const uint8_t *
                          void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
 {
     // validate everything both launches need before launching anything
-    if (int st = decode_args_status(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
+    if (int st = tkv_decode_check_args(desc, n_items, batch, n_q_heads, workspace, workspace_bytes)) return st;
     if (batch == 0) return TKV_OK;
     if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return TKV_ERR_INVALID_ARG;
     if (!q || !out || !page_indptr || !n_tok_int2 || !n_tok_int4 || !seq_item_indptr) return TKV_ERR_INVALID_ARG;

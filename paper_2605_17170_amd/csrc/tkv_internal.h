@@ -25,4 +25,9 @@ int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_
 int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indptr, int32_t n_items, int32_t batch,
                              int32_t n_q_heads, float *out, const void *workspace, void *stream);
 
+
+// Argument checks shared by the decode entry points (tkv_host.cpp); TKV_OK or a negative status.
+int tkv_decode_check_args(const tkv_desc *desc, int32_t n_items, int32_t batch, int32_t n_q_heads,
+                          const void *workspace, size_t workspace_bytes);
+
 #endif

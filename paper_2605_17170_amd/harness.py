@@ -112,6 +112,16 @@ class PagedCache:
                                  float(sm_scale), out, workspace, self.status, stream)
         return out
 
+    def decode_static(self, q: torch.Tensor, out: torch.Tensor, pool=None, stream=None):
+        """D2-D7 with the partials in the library's fixed device array: nothing is allocated here either
+        (`out` comes from the caller)."""
+        d_items, d_sip, _, _ = self._plan
+        sm_scale = np.float32(1.0 / math.sqrt(tkv.HEAD_DIM))
+        tkv.tkv_decode_attention_static(self.desc, self.pool if pool is None else pool, self.bit_map, q,
+                                        self.d_page_indptr, self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items,
+                                        d_sip, float(sm_scale), out, self.status, stream)
+        return out
+
     def decode_split(self, q: torch.Tensor, workspace, pool=None, stream=None):
         """D2-D6 only (used by the benchmark to time the split kernel by itself)."""
         d_items = self._plan[0]

@@ -40,7 +40,7 @@ EXPORTS = [
     "tkv_seq_create", "tkv_seq_destroy", "tkv_seq_release", "tkv_seq_n_tokens", "tkv_seq_n_pages",
     "tkv_seq_page_ids", "tkv_route_residual", "tkv_plan_append_max_work", "tkv_plan_append", "tkv_quantize_append", "tkv_gather_dequant",
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
-    "tkv_decode_split", "tkv_decode_reduce", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
+    "tkv_decode_split", "tkv_decode_reduce", "tkv_decode_attention_static", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
     "tkv_tag_tokens", "tkv_tags_to_bits", "tkv_tag_counts", "tkv_probe_stream_read",
 ]
 
@@ -117,6 +117,8 @@ def lib():
         L.tkv_decode_workspace_bytes.argtypes = [dp, i32, i32]
         L.tkv_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float,
                                            vp, vp, sz, vp, vp]
+        L.tkv_decode_attention_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float,
+                                                  vp, vp, vp]
         L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
         L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
         L.tkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -344,6 +346,28 @@ def tkv_decode_attention(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_in
                                       _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
                                       _dev(out), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
            "tkv_decode_attention")
+
+
+TKV_DECODE_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def tkv_decode_attention_static(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
+                                seq_item_indptr, sm_scale: float, out, status=None, stream=None):
+    """tkv_decode_attention with the partials in the library's fixed device array (no workspace argument,
+    nothing allocated); same device tensors otherwise."""
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    n_items = int(items.shape[0]) if items is not None else 0
+    assert q.element_size() == 2 and int(q.shape[2]) == desc.head_dim
+    assert page_indptr.numel() == batch + 1 and seq_item_indptr.numel() == batch + 1
+    assert n_tok_int2.numel() == batch and n_tok_int4.numel() == batch
+    assert out.numel() == batch * n_q_heads * desc.head_dim and out.element_size() == 4
+    if n_items:
+        assert items.numel() == 4 * n_items and pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
+    _check(lib().tkv_decode_attention_static(C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr),
+                                             _dev(page_ids), _dev(n_tok_int2), _dev(n_tok_int4), _dev(items),
+                                             _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
+                                             _dev(out), _dev(status), _stream(stream)),
+           "tkv_decode_attention_static")
 
 
 def tkv_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, sm_scale: float,
