@@ -49,7 +49,10 @@ enum {
     TKV_STATUS_BITMAP_MISMATCH = 2,  /* decode: bit_map[page] differs from the width its position implies (page skipped) */
     TKV_STATUS_PAGE_RANGE = 4,       /* a page id read on the device lies outside the pool (page skipped) */
     TKV_STATUS_DST_RANGE = 8,        /* tkv_gather_dequant: an output row index >= n_tokens (slot skipped) */
-    TKV_STATUS_BLOCK_PARTIAL = 16    /* append, per-channel INT2 keys: a 32-token block arrived incomplete (block skipped) */
+    TKV_STATUS_BLOCK_PARTIAL = 16,   /* append, per-channel INT2 keys: a 32-token block arrived incomplete (block skipped) */
+    TKV_STATUS_SCALE_SATURATED = 32, /* decode: a stored V scale above 255, or a per-channel INT2 key scale above 1023, was
+                                        clamped: the output is finite but not the attention over the stored values */
+    TKV_STATUS_BAD_ITEM = 64         /* decode: a work item names a sequence outside the batch (it contributes nothing) */
 };
 
 const char *tkv_strerror(int status);

@@ -1,11 +1,11 @@
 // tkv_decode_attention: split-K flash-decoding over the paged INT2 / INT4 KV
 // pool with in-register dequantisation, and the cross-split reduction
-// (paper Sec. 3.2.3 "Decode": KV processed as parallel contiguous splits,
-// each running one dequantisation path, merged by online log-sum-exp).
+// (paper Sec. 3.2.3 "Decode").
 //
 // One wavefront owns one (work item, kv head): a contiguous range of one
 // sequence's page list.  All query heads that share the kv head (up to 8)
-// are processed together so the packed KV bytes are read from HBM once.
+// are processed together so the packed KV bytes are read from HBM once; the
+// partials (m, l, acc) of the items are merged by tkv_reduce_kernel.
 //
 // Matrix cores do both contractions (v_mfma_f32_16x16x32_f16), fp32 accumulate,
 // and the packed codes are never expanded by arithmetic: a masked 16-bit field
@@ -19,20 +19,26 @@
 //         result.  The zero-point term sum_g zero[token,g] * sum_{c in g} q[head,c]
 //         is one more MFMA whose A operand is the stored fp16 zero plane.
 //         Head columns 8..15 repeat heads 0..7.
-//   PV    D[head, channel] = sum_token (P[head, token] * scale[token, g]) * code[token, channel]
-//         The V scale multiplies P, not the codes.  The softmax weights must be
-//         good to about 2^-17 (a group with outliers has |code * scale| and
-//         |zero| of tens while the tolerance near 0 is 2e-3), so P is split into
-//         two fp16 pieces that occupy the 16 MFMA rows (8 heads x {hi, lo});
-//         row hi carries fp16(P_hi * scale), row lo carries P_lo * scale plus
-//         the exact remainder of the hi product, and the epilogue adds the two
-//         rows.  The zero-point term sum_token P * zero[token, g] and the
-//         softmax denominator come from one extra MFMA of the same P pieces
-//         against the zero plane and a column of ones.
+//   PV    D[(head, half), channel] = sum_token a[head, token, g] * code[token, channel],
+//         a = fp16(W * scale[token, g]), W the softmax weight in fp16: the V scale
+//         multiplies the weights, not the codes.  Rows 0..7 carry the weights of the
+//         heads for groups 0 and 1, rows 8..15 for groups 2 and 3; the 16 columns of
+//         an MFMA are 8 channels of groups {0,1} and 8 channels of groups {2,3}
+//         (each lane loads its V words accordingly), so every (head, token, group)
+//         product is formed once per wavefront; the two cross quadrants of the
+//         result are never read.
+//         Dequantised value: x = s*c + z = s*(c - c0) + (z + s*c0) for ANY c0.  With
+//         c0 = round(-z/s) the remainder z' = z + s*c0 is at most s/2, and the two
+//         large terms s*c and s*c0 are weighted by the SAME rounded a, so their
+//         cancellation is exact: sum_t a*c0 is one more MFMA (c0 in the slot
+//         encoding of the codes), sum_t W*z' another (z' in two fp16 pieces) whose
+//         ninth column of ones gives the softmax denominator.  The rounding of a
+//         perturbs a token's weight for one group by 2^-12 relative, which moves the
+//         output by at most that fraction of the token's dequantised values.
 //
 // Every product the MFMAs see is exact; the roundings are fp32 accumulation,
-// the fp32 K-scale multiply, the 22-bit split of P and the 2^-22 relative
-// rounding of the lo row.
+// the fp32 K-scale multiply, the 11-bit softmax weight (common to numerator and
+// denominator) and the 11-bit a.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -56,8 +62,8 @@ typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 #endif
 
 constexpr float kTau = 4.0f;   // rescale when a logit exceeds the reference maximum by this much (log2 units)
-// Softmax weights are carried as W = P * 2^kPExp (P <= 2^kTau), so that the lo piece of a small weight
-// stays clear of the fp16 subnormal grid; numerator and denominator share the factor.
+// Softmax weights are carried in fp16 as W = P * 2^kPExp (P <= 2^kTau), so that small weights stay clear
+// of the fp16 subnormal grid; numerator and denominator share the factor.
 constexpr int kPExp = 8;
 // The V scale is staged as scale * 2^(kVExp - pos), pos = bit position of the code's field in its fp16 half; undone once in the epilogue.
 constexpr int kVExp = -1;
@@ -96,14 +102,6 @@ template <int HALF> __device__ __forceinline__ float residual(uint32_t t2, float
     else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(t2), "v"(negk), "v"(p));
     return r;
 }
-// One fp16 piece of (p0, p1): lanes with negk = 0 get the leading 11 bits (truncated), lanes with
-// negk = -1 the next 11 bits of the remainder.  `hi` receives the leading piece in every lane.
-__device__ __forceinline__ uint32_t p_piece(float p0, float p1, float negk, uint32_t &hi)
-{
-    hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p0, p1));
-    const float r0 = residual<0>(hi, negk, p0), r1 = residual<1>(hi, negk, p1);
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r0, r1));
-}
 __device__ __forceinline__ uint32_t pk_fma(uint32_t x, uint32_t y, uint32_t z)   // x * y + z per fp16 half, one rounding
 {
     const half2_t r = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, x), __builtin_bit_cast(half2_t, y),
@@ -124,6 +122,10 @@ __device__ __forceinline__ float row_ror8(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
 }
+__device__ __forceinline__ uint32_t ror8_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+}
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll
@@ -140,11 +142,18 @@ __device__ __forceinline__ void lds_order()
 }
 
 struct WaveState {
-    floatx4 acc[8];     // PV accumulators: tile jt (16 channels) x rows 4*q4 + i = (head, piece of P)
-    floatx4 zacc;       // zero-term (cols 0..3 = groups) and denominator (col 4), same rows
+    // PV accumulators.  Lane (c = lane % 16, q4 = lane / 16) holds rows 4*q4 + i: head 4*(q4 & 1) + i of row half
+    // q4 >> 1; its column of acc[chunk][comp] is channel 64*(c >> 3) + 16*comp + (chunk ? c ^ 8 : c) % 16.
+    // Only the quadrants with q4 >> 1 == c >> 3 (row half = column half) are meaningful.
+    floatx4 acc[2][4];
+    floatx4 zp;         // sum_t W * zero[t, g] in columns 0..3 (groups), sum_t W in column 4
+    uint32_t sat;       // non-zero once a staged scale was clamped (reported in the status word at the end)
     float m_ref;        // reference maximum of this lane's head column, log2 units, -inf before the first page
 };
 
+// q operands of the QK^T MFMAs with two token sets: per (group, half group) 16 entries (sub*8 + head) and one of zeros
+constexpr int kQyStride = 17, kQyZero = 16;
+constexpr int kPvZ = 0, kPvS = 32, kPvZero = 64, kPvOne = 65, kPvChunks = 66;
 
 // Only the kernel for per-channel INT2 keys holds the second q operand.
 template <bool KC> struct LdsExtra {};
@@ -156,95 +165,154 @@ template <bool KC> struct alignas(16) Lds : LdsExtra<KC> {
     // K zero plane (512 B) of the page as stored, kz a plane of zeros (the INT4 pages, which come later in
     // an item, overwrite all three with their own staging).
     alignas(16) float ks[kPageTokens * kGroups];         // K scale * F, fp32 [token][group]
-    alignas(16) uint32_t vs[kPageTokens * kGroups / 2];  // V scale * 2^(kVExp - pos), fp16 pairs in plane order
-    alignas(16) uint32_t vz[kPageTokens * kGroups / 2];  // V zero, fp16 pairs in plane order
-    alignas(16) uint2 kz[kPageTokens];                   // K zero, four fp16 per token
-    alignas(16) uint4 qo[kGroups][64];                   // B operand of the QK^T MFMAs per group and lane
+    // Operands of the PV phase, 16-byte chunks of eight fp16 (the tokens of one k-slot octet), one array so that
+    // a lane-dependent index can choose between staged data and the constants:
+    //   kPvZ + (blk*4 + quad)*4 + g   V zero, as stored
+    //   kPvS + (blk*4 + quad)*4 + g   V scale * 2^(kVExp - pos)
+    //   kPvZero   zeros;   kPvOne   ones
+    alignas(16) uint4 pv[kPvChunks];
+    // K zero, four fp16 per token (per-channel INT2 keys, which also use it as a plane of zeros; otherwise the K
+    // zeros travel between lanes without a copy in LDS)
+    alignas(16) uint2 kz[KC ? kPageTokens : 2];
+    // B operands of the QK^T MFMAs: per group and lane (per-channel INT2 keys), or 8 x (16 entries + zeros) (build_q_operand)
+    alignas(16) uint4 qo[KC ? kGroups : 2][KC ? 64 : 4 * kQyStride];
     alignas(16) float alpha[16];
-    alignas(16) float zl[8][8];
+    // [head][8] floats of the prologue (group sums of q) and the epilogue (zero-point sums, denominator): the q
+    // operands are not live then
+    __device__ __forceinline__ float (*zl())[8] { return reinterpret_cast<float(*)[8]>(qo); }
     __device__ __forceinline__ uint4 *kc_scale() { return reinterpret_cast<uint4 *>(ks); }
     __device__ __forceinline__ uint4 *kc_zero() { return reinterpret_cast<uint4 *>(ks) + 32; }
     __device__ __forceinline__ uint4 *kc_nil() { return reinterpret_cast<uint4 *>(kz); }
 };
 
-// B operand of the QK^T MFMAs for one width, kept in LDS: per group and lane, 4 registers of fp16
-// pairs holding q' = q * 2^E * 2^-pos in the slot order the unpack produces.
+// B operand of the QK^T MFMAs for one width, kept in LDS: 4 registers of fp16 pairs holding
+// q' = q * 2^E * 2^-pos in the slot order the unpack produces.
+//  - per-channel INT2 keys: per group and lane (head columns 8..15 repeat heads 0..7), plus the copy without
+//    slot factors;
+//  - otherwise (two token sets, see compute_page): per (group, half group) one entry per (channel octet sub,
+//    head) and an entry of zeros, which the lanes whose k-slots belong to the other token set read.
 template <int BITS, bool KC, class QF>
 __device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head, 128 values q * 2^E in LDS */, int q4,
                                                int lane, Lds<KC> &lds)
 {
+    if constexpr (KC && BITS == 2) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        uint32_t r[4], rp[4] = {0, 0, 0, 0};
-        (void)rp;
+        for (int g = 0; g < 4; ++g) {
+            uint32_t r[4], rp[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            int c0, c1;
-            float f;
-            if (BITS == 4) {
-                // registers: (n0,n4) (n1,n5)*16 (n2,n6) (n3,n7)*16 of the 8-channel word q4
-                const int nib = (k & 1) + 2 * (k >> 1);
-                c0 = 32 * g + 8 * q4 + nib;
-                c1 = c0 + 4;
-                f = (k & 1) ? 0.0625f : 1.0f;
-            } else {
+            for (int k = 0; k < 4; ++k) {
                 // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^(2k+3) of the 16-channel word q4/2
-                c0 = 32 * g + 16 * (q4 >> 1) + 4 * (q4 & 1) + k;
-                c1 = c0 + 8;
+                const int c0 = 32 * g + 16 * (q4 >> 1) + 4 * (q4 & 1) + k, c1 = c0 + 8;
                 // the unpack leaves the field of slot k at bit 2k + 3 (see compute_page)
-                f = 1.0f / (float)(1 << (2 * k + 3));
+                const float f = 1.0f / (float)(1 << (2 * k + 3));
+                r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
+                rp[k] = pack_h2((float)qf[c0], (float)qf[c1]);
             }
-            r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
-            if constexpr (KC && BITS == 2) rp[k] = pack_h2((float)qf[c0], (float)qf[c1]);
+            lds.qo[g][lane] = make_uint4(r[0], r[1], r[2], r[3]);
+            lds.qp[g][lane] = make_uint4(rp[0], rp[1], rp[2], rp[3]);
         }
-        lds.qo[g][lane] = make_uint4(r[0], r[1], r[2], r[3]);
-        if constexpr (KC && BITS == 2) lds.qp[g][lane] = make_uint4(rp[0], rp[1], rp[2], rp[3]);
+    } else {
+        uint4 *qy = reinterpret_cast<uint4 *>(lds.qo);
+        const int sub = q4 & 1, ent = sub * 8 + (lane & 7);   // lanes that differ in lane & 8 or q4 & 2 write the same entry
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int hg = 0; hg < 2; ++hg) {
+                uint32_t r[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    int c0, c1;
+                    float f;
+                    if (BITS == 4) {
+                        // registers: (n0,n4) (n1,n5)*16 (n2,n6) (n3,n7)*16 of the 8-channel word 2*hg + sub of the group
+                        const int nib = (k & 1) + 2 * (k >> 1);
+                        c0 = 32 * g + 8 * (2 * hg + sub) + nib;
+                        c1 = c0 + 4;
+                        f = (k & 1) ? 0.0625f : 1.0f;
+                    } else {
+                        // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^(2k+3) of the 16-channel word hg of the group
+                        c0 = 32 * g + 16 * hg + 4 * sub + k;
+                        c1 = c0 + 8;
+                        f = 1.0f / (float)(1 << (2 * k + 3));
+                    }
+                    r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
+                }
+                qy[(g * 2 + hg) * kQyStride + ent] = make_uint4(r[0], r[1], r[2], r[3]);
+            }
+        if (lane < 8) qy[lane * kQyStride + kQyZero] = make_uint4(0u, 0u, 0u, 0u);
     }
 }
 
 // Everything one wavefront loads for one (page, kv head) record.
 template <int BITS> struct PageRegs {
-    uint4 kw[4];          // K codes: one 16-byte chunk per 16-token tile (four groups of this lane's channel slice)
-    uint4 vw[BITS];       // V codes: 16-byte chunks, one word per 16-channel tile
+    uint4 kw[4];          // K codes, 16-byte chunks of four group words: [blk*2 + half group] of this lane's token (two token
+                          // sets), or one per 16-token tile (per-channel INT2 keys)
+    uint4 vw[BITS];       // V codes: 16-byte chunks, one word per 16-channel tile; [blk*2 + chunk] (INT4), [chunk] (INT2)
     uint2 ksc, vsc, vzc;  // this lane's four entries of the K scale / V scale / V zero planes
     uint2 kzc;            // K zero of token `lane`, four groups
     uint32_t bm;          // bit_map entry of the page
 };
 
-// The loads of one record come in two parts, issued as soon as the registers they land in are free:
-// part A (K codes, K zero, the three metadata planes, the bit_map entry) after the QK^T phase of the
-// previous page, part B (V codes) after its PV phase.
+// The loads of one record come in two parts, issued as soon as the registers they land in are free: the
+// metadata planes and the K codes after the QK^T phase of the previous page, the V codes after its PV phase.
 template <int BITS>
-__device__ __forceinline__ void load_page_a(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec,
-                                            const uint8_t *__restrict__ bit_map, int page, int lane)
+__device__ __forceinline__ void load_page_meta(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec,
+                                               const uint8_t *__restrict__ bit_map, int page, int lane, int opaque_zero)
 {
     using R = Rec<BITS>;
-    const int r16 = lane & 15, q4 = lane >> 4;
-    const uint4 *kc = reinterpret_cast<const uint4 *>(rec + R::kKCodes);
     pr.ksc = reinterpret_cast<const uint2 *>(rec + R::kKScale)[lane];
     pr.vsc = reinterpret_cast<const uint2 *>(rec + R::kVScale)[lane];
     pr.vzc = reinterpret_cast<const uint2 *>(rec + R::kVZero)[lane];
-    pr.bm = bit_map[page];
+    // `opaque_zero` is 0 in a register the compiler cannot see through: the load stays a per-lane load whose
+    // result is waited for where it is used, not a scalar value that is fetched back right behind the request
+    pr.bm = bit_map[page + opaque_zero];
     pr.kzc = reinterpret_cast<const uint2 *>(rec + R::kKZero)[lane];
+}
+// Index (16-byte chunks) of part i of this lane's K codes / V codes in the record's code plane.
+template <int BITS, bool KC> __device__ __forceinline__ int kcode_chunk(int i, int lane)
+{
+    const int r16 = lane & 15, q4 = lane >> 4;
+    if constexpr (KC && BITS == 2) return i * 32 + (q4 >> 1) * 16 + r16;   // tile i
+    // k-slots 0..15 of an MFMA are the first token set (tile 2*blk), 16..31 the second (tile 2*blk + 1); a lane
+    // holds eight channels: octet q4 & 1 of half group hg; i = blk*2 + hg
+    const int tile = 2 * (i >> 1) + (q4 >> 1), hg = i & 1;
+    return BITS == 4 ? tile * 64 + (2 * hg + (q4 & 1)) * 16 + r16 : (tile * 2 + hg) * 16 + r16;
+}
+template <int BITS> __device__ __forceinline__ int vcode_chunk(int i, int lane)
+{
+    // Columns 0..7 of the PV MFMAs are channels of groups 0 and 1, columns 8..15 of groups 2 and 3: lane
+    // (c, quad) reads the chunks of channel half c >> 3, at its own column (even i) and at column c ^ 8 (odd i);
+    // INT4: i = blk*2 + chunk, INT2: i = chunk (a word holds both blocks)
+    const int base = ((lane & 8) << 3) + (lane & 48) + ((lane & 15) ^ ((i & 1) << 3));
+    return BITS == 4 ? (i >> 1) * 128 + base : base;
+}
+template <int BITS, bool KC>
+__device__ __forceinline__ void load_page_k(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec, int lane)
+{
+    const uint4 *kc = reinterpret_cast<const uint4 *>(rec + Rec<BITS>::kKCodes);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) pr.kw[e] = BITS == 4 ? kc[e * 64 + lane] : kc[e * 32 + (q4 >> 1) * 16 + r16];
+    for (int i = 0; i < 4; ++i) pr.kw[i] = kc[kcode_chunk<BITS, KC>(i, lane)];
 }
 template <int BITS>
-__device__ __forceinline__ void load_page_b(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec, int lane)
+__device__ __forceinline__ void load_page_v(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec, int lane)
 {
-    using R = Rec<BITS>;
-    const uint4 *vc = reinterpret_cast<const uint4 *>(rec + R::kVCodes);
+    const uint4 *vc = reinterpret_cast<const uint4 *>(rec + Rec<BITS>::kVCodes);
 #pragma unroll
-    for (int i = 0; i < BITS; ++i) pr.vw[i] = vc[i * 64 + lane];
+    for (int i = 0; i < BITS; ++i) pr.vw[i] = vc[vcode_chunk<BITS>(i, lane)];
 }
-
 // Lane constants of the page loop.
 struct LaneConst {
     float F;              // 2^(24 - E): undoes the subnormal position and the power-of-two normalisation of q
     float kappa;          // sm_scale * log2(e)
-    uint32_t vmul01, vmul23;   // fp16 pairs of the staging factor of the V scale
-    float negk;           // 0 in head columns 0..7 (hi piece of P), -1 in columns 8..15 (lo piece)
-    uint32_t lomask;      // 0 / all ones likewise
+    uint32_t vmul01, vmul23;   // fp16 pairs of the staging factor of the V scale, 2^(kVExp - pos)
+    int zp_idx[2];        // chunk of Lds::pv with this lane's B operand of the zero-point MFMA, per 32-token block
+    int vs_idx;           // ... of the staged V scales of (block 0, this lane's quad, group 2*(c >> 3))
+    int vs_st;            // 8-byte slot of Lds::pv (behind kPvS) where this lane stages its four V scales
+    uint32_t vrot[2];     // INT4 V unpack: rotate amounts that bring registers 0, 1 / 2, 3 of the operand into place
+    uint32_t vmask[4];    // INT2 V unpack: field masks of operand registers 0..3
+    int opaque_zero;      // 0, opaque to the compiler
+    int tok0;             // two token sets: first token of this lane's four within a 32-token block
+    int qy_ent;           // ... entry of this lane in a q operand of the QK^T MFMAs (kQyZero: the zero entry)
     float zmul;           // per-channel INT2 keys: 2^-24 in head columns 0..7, 0 in columns 8..15
 };
 
@@ -260,6 +328,8 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     const bool partial = n_valid < kPageTokens;   // wave-uniform: only the last page of a width can be partly filled
 
     // ---- stage metadata in LDS --------------------------------------------
+    uint2 kzv[2] = {{0u, 0u}, {0u, 0u}};   // K zeros of this lane's MFMA row per 32-token block (two token sets)
+    (void)kzv;
     {
         uint2 vsc = pr.vsc, vzc = pr.vzc;
         if (partial) {
@@ -275,22 +345,38 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         }
         if constexpr (kPerChannel) {
             // the two key metadata planes as stored: fp16 [block][128 channel positions]
-            reinterpret_cast<uint2 *>(lds.kc_scale())[lane] = make_uint2(pk_min(pr.ksc.x, kKcClamp), pk_min(pr.ksc.y, kKcClamp));
+            const uint32_t k01 = pk_min(pr.ksc.x, kKcClamp), k23 = pk_min(pr.ksc.y, kKcClamp);
+            st.sat |= (k01 ^ pr.ksc.x) | (k23 ^ pr.ksc.y);
+            reinterpret_cast<uint2 *>(lds.kc_scale())[lane] = make_uint2(k01, k23);
             reinterpret_cast<uint2 *>(lds.kc_zero())[lane] = pr.kzc;
         } else {
             const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
             reinterpret_cast<float4 *>(lds.ks)[lane] =
                 make_float4((float)a[0] * lc.F, (float)a[1] * lc.F, (float)b[0] * lc.F, (float)b[1] * lc.F);
-            lds.kz[lane] = pr.kzc;
+            // K zeros: lane (r, q4) takes those of token 32*blk + 16*(q4 >> 1) + r, which lane number that token holds.
+            // An MFMA row holds a token of either set: a never-written token's zero-point (any bit pattern) would
+            // meet the zeros of the other set's columns in the same row and could make them NaN.
+            const uint2 kzm = partial && lane >= n_valid ? make_uint2(0u, 0u) : pr.kzc;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                const int src = 4 * (32 * blk + 16 * (q4 >> 1) + r16);
+                kzv[blk] = make_uint2((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
+                                      (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.y));
+            }
         }
-        reinterpret_cast<uint2 *>(lds.vs)[lane] =
-            make_uint2(pk_min(pk_mul(vsc.x, lc.vmul01), kVsClamp), pk_min(pk_mul(vsc.y, lc.vmul23), kVsClamp));
-        reinterpret_cast<uint2 *>(lds.vz)[lane] = vzc;
+        // V side, this lane's four (token, group) entries: the staged scale and the zero plane as stored
+        {
+            const uint32_t m01 = pk_mul(vsc.x, lc.vmul01), m23 = pk_mul(vsc.y, lc.vmul23);
+            const uint32_t s01 = pk_min(m01, kVsClamp), s23 = pk_min(m23, kVsClamp);
+            st.sat |= (s01 ^ m01) | (s23 ^ m23);
+            reinterpret_cast<uint2 *>(lds.pv)[2 * kPvS + lc.vs_st] = make_uint2(s01, s23);
+            reinterpret_cast<uint2 *>(lds.pv)[2 * kPvZ + lane] = vzc;
+        }
     }
     lds_order();
 
     // ---- QK^T: S[e][i] = q . k_hat (unscaled) for token 16e + 4*q4 + i, head column r16
-    floatx4 S[4];
+    floatx4 S[4];   // per-channel keys: tile e; else blocks 0, 1 only
     if constexpr (kPerChannel) {
         // score = sum_c (q_c s_c) code + sum_c q_c z_c with s, z of the token's block.  q s is formed per block
         // in two fp16 pieces, exactly (q has 8 significant bits, s 11): head columns 0..7 take
@@ -337,57 +423,73 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             asm volatile("" : "+v"(S[e]));
         }
         __builtin_amdgcn_sched_barrier(0);
-    } else
+    } else {
+        // Per-token groups.  The eight heads fill only half of the 16 MFMA columns, so the columns carry two
+        // token sets: rows r of a 32-token block are token 32*blk + r in columns 0..7 and token 32*blk + 16 + r in
+        // columns 8..15.  An MFMA contracts 16 channels (half a group) of both sets: k-slots 0..15 hold the
+        // codes of the first token, 16..31 those of the second, and the B operand holds q in the matching half
+        // of its k-slots and zeros in the other.  All that follows the MFMAs (K scale, exponentials, weight
+        // pieces) is then done once per (token, head).
+        const uint4 *qy = reinterpret_cast<const uint4 *>(lds.qo);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const uint2 kz = lds.kz[16 * e + r16];
-        const half8 za = as_half8(kz.x, kz.y, kz.x, kz.y);
-        floatx4 s = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
-        float4 sc[4];
+        for (int blk = 0; blk < 2; ++blk) {
+            const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].x, kzv[blk].y);
+            floatx4 s = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
+            float4 sc[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sc[i] = reinterpret_cast<const float4 *>(lds.ks)[16 * e + 4 * q4 + i];
-        const uint32_t w[4] = {pr.kw[e].x, pr.kw[e].y, pr.kw[e].z, pr.kw[e].w};
+            for (int i = 0; i < 4; ++i) sc[i] = reinterpret_cast<const float4 *>(lds.ks)[32 * blk + lc.tok0 + i];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            half8 a;
-            if (BITS == 4) {
-                const uint32_t w8 = w[g] >> 8;
-                a = as_half8(w[g] & 0x000f000fu, w[g] & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u);
-            } else {
-                // this lane's 16 codes of the word are its upper or lower half; the rotate leaves the fields at bits
-                // 4:3, 6:5, 8:7, 10:9 of each half (towards the top of the fp16 mantissa, as for V: the matrix core
-                // drops product bits below its alignment window), stray bits fall outside the masks
-                const uint32_t ws = __builtin_amdgcn_alignbit(w[g], w[g], (q4 & 1) ? 5u : 29u);
-                a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
+            for (int g = 0; g < 4; ++g) {
+                floatx4 p = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int hg = 0; hg < 2; ++hg) {
+                    const uint4 kw = pr.kw[blk * 2 + hg];
+                    const uint32_t w = g == 0 ? kw.x : g == 1 ? kw.y : g == 2 ? kw.z : kw.w;
+                    half8 a;
+                    if (BITS == 4) {
+                        const uint32_t w8 = w >> 8;
+                        a = as_half8(w & 0x000f000fu, w & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u);
+                    } else {
+                        // this lane's 8 codes of the word are its upper or lower half; the rotate leaves the fields at bits
+                        // 4:3, 6:5, 8:7, 10:9 of each half (towards the top of the fp16 mantissa, as for V: the matrix core
+                        // drops product bits below its alignment window), stray bits fall outside the masks
+                        const uint32_t ws = __builtin_amdgcn_alignbit(w, w, (q4 & 1) ? 5u : 29u);
+                        a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
+                    }
+                    const uint4 qb = qy[(g * 2 + hg) * kQyStride + lc.qy_ent];
+                    p = mfma(a, as_half8(qb.x, qb.y, qb.z, qb.w), p);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float scg = g == 0 ? sc[i].x : g == 1 ? sc[i].y : g == 2 ? sc[i].z : sc[i].w;
+                    s[i] = fmaf(scg, p[i], s[i]);
+                }
             }
-            const uint4 qb = lds.qo[g][lane];
-            const half8 b = as_half8(qb.x, qb.y, qb.z, qb.w);
-            const floatx4 p = mfma(a, b, floatx4{0.f, 0.f, 0.f, 0.f});
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float scg = g == 0 ? sc[i].x : g == 1 ? sc[i].y : g == 2 ? sc[i].z : sc[i].w;
-                s[i] = fmaf(scg, p[i], s[i]);
-            }
+            asm volatile("" : "+v"(s));   // the scaled sums are formed here, not sunk next to their first use
+            S[blk] = s;
+            __builtin_amdgcn_sched_barrier(0);   // one block's LDS operands at a time (register pressure)
         }
-        asm volatile("" : "+v"(s));   // the scaled sums are formed here, not sunk next to their first use
-        S[e] = s;
-        __builtin_amdgcn_sched_barrier(0);   // one tile's LDS operands at a time (register pressure)
     }
     after_qk();
+    constexpr int kS = kPerChannel ? 4 : 2;   // logit registers of this lane: 16 tokens (every column half the same) or 8
     if (partial) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+        for (int e = 0; e < kS; ++e)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) S[e][i] = 16 * e + 4 * q4 + i < n_valid ? S[e][i] : -INFINITY;
+            for (int i = 0; i < 4; ++i) {
+                const int t = kPerChannel ? 16 * e + 4 * q4 + i : 32 * e + lc.tok0 + i;
+                S[e][i] = t < n_valid ? S[e][i] : -INFINITY;
+            }
     }
 
     // ---- online softmax with a lazily updated reference maximum ------------
-    // The cheap test looks only at this lane's own 16 logits; the column maximum is formed across
+    // The cheap test looks only at this lane's own logits; the column maximum is formed across
     // lanes only when some lane needs a new reference.
     float mx = fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3]));
 #pragma unroll
-    for (int e = 1; e < 4; ++e) mx = fmaxf(fmaxf(mx, S[e][0]), fmaxf(fmaxf(S[e][1], S[e][2]), S[e][3]));
+    for (int e = 1; e < kS; ++e) mx = fmaxf(fmaxf(mx, S[e][0]), fmaxf(fmaxf(S[e][1], S[e][2]), S[e][3]));
     if (__any(mx * lc.kappa > st.m_ref + kTau)) {
+        if constexpr (!kPerChannel) mx = fmaxf(mx, row_ror8(mx));   // the other token set of the head
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(st.m_ref, mx * lc.kappa);
@@ -398,85 +500,149 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         const float4 al = reinterpret_cast<const float4 *>(lds.alpha)[q4 & 1];   // rows 4*q4 .. 4*q4+3 -> heads (4*q4 + i) & 7
         const floatx4 av = {al.x, al.y, al.z, al.w};
 #pragma unroll
-        for (int jt = 0; jt < 8; ++jt) st.acc[jt] *= av;
-        st.zacc *= av;
+        for (int j = 0; j < 8; ++j) st.acc[j >> 2][j & 3] *= av;
+        st.zp *= av;
     }
     const float nmref = (float)kPExp - (st.m_ref == -INFINITY ? 0.0f : st.m_ref);
-    uint32_t pa[2][4];   // this lane's piece of P (hi in head columns 0..7, lo in 8..15): A operand of the zero / denominator MFMA
-    uint32_t py[2][4];   // the hi piece again in the lo columns, 0 in the hi columns
+    // W = P * 2^kPExp in two fp16 pieces (leading 11 bits truncated, then the next 11): the eight tokens of this
+    // lane's k-slot octet per 32-token block.  With two token sets a lane forms the pieces of its own four tokens
+    // and takes the other four from the lane eight columns on: registers 0, 1 are its own, 2, 3 the other set's
+    // (the V operand of columns 8..15 lists its tokens in that order too).
+    uint32_t wh[2][4], wl[2][4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < kS; ++e) {
         float pv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv[i] = __builtin_amdgcn_exp2f(fmaf(S[e][i], lc.kappa, nmref));
-        uint32_t h01, h23;
-        pa[e >> 1][2 * (e & 1)] = p_piece(pv[0], pv[1], lc.negk, h01);
-        pa[e >> 1][2 * (e & 1) + 1] = p_piece(pv[2], pv[3], lc.negk, h23);
-        py[e >> 1][2 * (e & 1)] = h01 & lc.lomask;
-        py[e >> 1][2 * (e & 1) + 1] = h23 & lc.lomask;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pv[2 * k], pv[2 * k + 1]));
+            const uint32_t lo = __builtin_bit_cast(
+                uint32_t, __builtin_amdgcn_cvt_pkrtz(residual<0>(hi, -1.0f, pv[2 * k]), residual<1>(hi, -1.0f, pv[2 * k + 1])));
+            if constexpr (kPerChannel) {
+                wh[e >> 1][2 * (e & 1) + k] = hi;
+                wl[e >> 1][2 * (e & 1) + k] = lo;
+            } else {
+                wh[e][k] = hi;
+                wl[e][k] = lo;
+                wh[e][2 + k] = ror8_u32(hi);
+                wl[e][2 + k] = ror8_u32(lo);
+            }
+        }
     }
 
     // ---- PV ------------------------------------------------------------------
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
-        // zero term and denominator: columns 0..3 = groups, column 4 = ones
+        // zero-point term and denominator: columns 0..3 = V zero of the groups, column 4 = ones
         {
-            uint4 bz = reinterpret_cast<const uint4 *>(lds.vz)[(blk * 4 + q4) * 4 + (r16 & 3)];
-            if (r16 >= 4) {
-                const uint32_t c = r16 == 4 ? 0x3c003c00u : 0u;
-                bz = make_uint4(c, c, c, c);
-            }
-            st.zacc = mfma(as_half8(pa[blk][0], pa[blk][1], pa[blk][2], pa[blk][3]), as_half8(bz.x, bz.y, bz.z, bz.w), st.zacc);
+            const uint4 bz4 = lds.pv[lc.zp_idx[blk]];
+            const half8 bz = as_half8(bz4.x, bz4.y, bz4.z, bz4.w);
+            st.zp = mfma(as_half8(wh[blk][0], wh[blk][1], wh[blk][2], wh[blk][3]), bz, st.zp);
+            st.zp = mfma(as_half8(wl[blk][0], wl[blk][1], wl[blk][2], wl[blk][3]), bz, st.zp);
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const uint4 vs = reinterpret_cast<const uint4 *>(lds.vs)[(blk * 4 + q4) * 4 + g];
+        for (int gg = 0; gg < 2; ++gg) {
+            // a = W * scale for group 2*(c >> 3) + gg in two fp16 pieces: hi = fp16(W_hi s), lo = W_lo s + the exact
+            // remainder of the hi product
+            const uint4 vs = lds.pv[lc.vs_idx + 16 * blk + gg];
             const uint32_t vsr[4] = {vs.x, vs.y, vs.z, vs.w};
-            uint32_t ar[4];
+            uint32_t ah[4], al[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                // hi rows: fp16(P_hi * scale); lo rows: P_lo * scale + (P_hi * scale - fp16(P_hi * scale))
-                const uint32_t t = pk_mul(py[blk][k], vsr[k]);
-                ar[k] = pk_fma(pa[blk][k], vsr[k], pk_rem(py[blk][k], vsr[k], t));
+                ah[k] = pk_mul(wh[blk][k], vsr[k]);
+                al[k] = pk_fma(wl[blk][k], vsr[k], pk_rem(wh[blk][k], vsr[k], ah[k]));
             }
-            const half8 a = as_half8(ar[0], ar[1], ar[2], ar[3]);
+            const half8 a_hi = as_half8(ah[0], ah[1], ah[2], ah[3]), a_lo = as_half8(al[0], al[1], al[2], al[3]);
+            half8 b[2][2];
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                const int jt = 2 * g + t2;
-                uint32_t w;
-                {
-                    const uint4 v = BITS == 4 ? pr.vw[blk * 2 + (jt >> 2)] : pr.vw[jt >> 2];
-                    w = (jt & 3) == 0 ? v.x : (jt & 3) == 1 ? v.y : (jt & 3) == 2 ? v.z : v.w;
+            for (int chunk = 0; chunk < 2; ++chunk)
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    const int comp = 2 * gg + cc;
+                    const uint4 v = BITS == 4 ? pr.vw[blk * 2 + chunk] : pr.vw[chunk];
+                    const uint32_t w = comp == 0 ? v.x : comp == 1 ? v.y : comp == 2 ? v.z : v.w;
+                    // Codes as fp16 subnormals, fields shifted towards the top of the mantissa (INT2: bits 4:3,
+                    // 6:5, 8:7, 10:9 of each half; INT4: bits 6:3 and 10:7): the matrix core aligns the products of
+                    // a lane's eight k-slots to the largest exponent *field* and drops what falls below a fixed
+                    // window, so leading zeros of a subnormal cost precision.  Bit 10 is the lowest exponent bit:
+                    // fp16 is linear through the first binade, so a field may reach it.  The slot's power of two
+                    // is undone in the staged V scale.
+                    // Registers 0, 1 take the tokens of this lane's own set, 2, 3 those of the other set (see the
+                    // weights): the rotate amounts (INT4) or the masks (INT2) differ between the column halves.
+                    if (BITS == 4) {
+                        const uint32_t wa = __builtin_amdgcn_alignbit(w, w, lc.vrot[0]), wb = __builtin_amdgcn_alignbit(w, w, lc.vrot[1]);
+                        b[chunk][cc] = as_half8(wa & 0x00780078u, wa & 0x07800780u, wb & 0x00780078u, wb & 0x07800780u);
+                    } else {
+                        const uint32_t ws = blk ? (w >> 5) : (w << 3);
+                        b[chunk][cc] = as_half8(ws & lc.vmask[0], ws & lc.vmask[1], ws & lc.vmask[2], ws & lc.vmask[3]);
+                    }
+                    st.acc[chunk][2 * gg + cc] = mfma(a_hi, b[chunk][cc], st.acc[chunk][2 * gg + cc]);
                 }
-                // Codes as fp16 subnormals, fields shifted towards the top of the mantissa (INT2: bits 4:3,
-                // 6:5, 8:7, 10:9 of each half; INT4: bits 6:3 and 10:7): the matrix core aligns the products of
-                // a lane's eight k-slots to the largest exponent *field* and drops what falls below a fixed
-                // window, so leading zeros of a subnormal cost precision.  Bit 10 is the lowest exponent bit:
-                // fp16 is linear through the first binade, so a field may reach it.  The slot's power of two
-                // is undone in the staged V scale.
-                half8 b;
-                if (BITS == 4) {
-                    const uint32_t wl = w << 3, wr = w >> 5;
-                    b = as_half8(wl & 0x00780078u, wl & 0x07800780u, wr & 0x00780078u, wr & 0x07800780u);
-                } else {
-                    const uint32_t ws = blk ? (w >> 5) : (w << 3);
-                    b = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
-                }
-                st.acc[jt] = mfma(a, b, st.acc[jt]);
-            }
+#pragma unroll
+            for (int chunk = 0; chunk < 2; ++chunk)
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) st.acc[chunk][2 * gg + cc] = mfma(a_lo, b[chunk][cc], st.acc[chunk][2 * gg + cc]);
         }
     }
     after_pv();
 }
 
 // All pages [pb, pe) of one width (indices into the sequence's page list).
-template <int BITS, bool KC>
-__device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, const uint8_t *__restrict__ bit_map,
-                                          const int32_t *__restrict__ pages, int pb, int pe, int last_index,
-                                          int last_valid, int page_lo, int page_hi, int n_pages_total, int kvh,
-                                          int n_kv_heads, int n_pages_int2, int item_end, int item_pages, int lane, half8 qz,
-                                          LaneConst lc, WaveState &st, Lds<KC> &lds, int32_t *status)
+// What stays the same for every page of a work item, and the pages of one width in it.
+struct ItemCtx {
+    const uint8_t *__restrict__ pool;
+    const uint8_t *__restrict__ bit_map;
+    const int32_t *__restrict__ pages;   // the sequence's page list
+    int kvh, n_kv_heads, n_pages_int2, n_pages_total, lane, opaque_zero;
+    int32_t *status;
+};
+struct WidthRange {
+    int pb, pe;                  // positions in the page list
+    int last_index, last_valid;  // position of the width's last page in the sequence and its number of valid tokens
+    int page_lo, page_hi;        // the pool's page ids
+};
+// Page id of list position pi (already loaded) and its number of valid tokens.  A page id outside its pool cannot
+// be addressed: it is flagged, a valid page is read instead and skipped.
+__device__ __forceinline__ int validate_page(const ItemCtx &cx, const WidthRange &wr, int pi, int &page)
 {
+    const bool ok = page >= wr.page_lo && page < wr.page_hi;
+    if (!ok) {
+        if (cx.status && cx.lane == 0)
+            atomicOr(cx.status, page < 0 || page >= cx.n_pages_total ? TKV_STATUS_PAGE_RANGE : TKV_STATUS_BITMAP_MISMATCH);
+        page = wr.page_lo;
+    }
+    return ok ? (pi == wr.last_index ? wr.last_valid : kPageTokens) : 0;
+}
+// State handed from start_pages to run_pages: the first record's registers, the next page's id.
+template <int BITS> struct Started {
+    PageRegs<BITS> pr;
+    int nv, page_next, nv_next;
+};
+// Requests the first record of a width.
+template <int BITS, bool KC>
+__device__ __forceinline__ void start_pages(const ItemCtx &cx, const WidthRange &wr, Started<BITS> &s0)
+{
+    int page = __builtin_amdgcn_readfirstlane(cx.pages[wr.pb]);
+    s0.nv = validate_page(cx, wr, wr.pb, page);
+    const int pi1 = wr.pb + 1 < wr.pe ? wr.pb + 1 : wr.pb;
+    s0.page_next = __builtin_amdgcn_readfirstlane(cx.pages[pi1]);
+    s0.nv_next = validate_page(cx, wr, pi1, s0.page_next);
+    const uint8_t *rec = cx.pool + record_offset(page, cx.kvh, cx.n_kv_heads, cx.n_pages_int2);
+    load_page_meta<BITS>(s0.pr, rec, cx.bit_map, page, cx.lane, cx.opaque_zero);
+    load_page_k<BITS, KC>(s0.pr, rec, cx.lane);
+    load_page_v<BITS>(s0.pr, rec, cx.lane);
+}
+
+template <int BITS, bool KC>
+__device__ __forceinline__ void run_pages(const ItemCtx &cx, const WidthRange &wr, Started<BITS> &s0, int item_end, int item_pages,
+                                          half8 qz, LaneConst lc, WaveState &st, Lds<KC> &lds)
+{
+    const uint8_t *__restrict__ pool = cx.pool;
+    const uint8_t *__restrict__ bit_map = cx.bit_map;
+    const int32_t *__restrict__ pages = cx.pages;
+    const int pb = wr.pb, pe = wr.pe, kvh = cx.kvh, n_kv_heads = cx.n_kv_heads, n_pages_int2 = cx.n_pages_int2, lane = cx.lane;
+    int32_t *status = cx.status;
     // A V code enters the MFMA as code * 2^(pos - 24), pos = lowest bit of its field after the unpack shift; the
     // staged scale of the slot carries 2^(kVExp - pos).  This lane stages plane entries 4*lane .. 4*lane+3 =
     // k-slots 4*(lane&1) + 0..3, i.e. operand registers 2*(lane&1) (first pair) and 2*(lane&1) + 1 (second pair).
@@ -486,27 +652,22 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
         const uint32_t h01 = (uint32_t)(15 + kVExp - p01) << 10, h23 = (uint32_t)(15 + kVExp - p23) << 10;
         lc.vmul01 = h01 | (h01 << 16);
         lc.vmul23 = h23 | (h23 << 16);
+        // Order of the eight tokens of a k-slot octet in the PV operands.  Per-channel INT2 keys: every lane lists
+        // the tokens of tile 2*blk first.  Two token sets: a lane lists its own set first, which for columns 8..15
+        // (the rows and columns of groups 2 and 3) is tile 2*blk + 1: those lanes swap the register pairs of the V
+        // operand, and the staged scales of groups 2 and 3 are stored with their 8-byte halves swapped.
+        const bool swap = !(KC && BITS == 2) && (lane & 8);
+        lc.vrot[0] = swap ? 5u : 29u;   // w >> 5 / w << 3 (stray bits fall outside the masks)
+        lc.vrot[1] = swap ? 29u : 5u;
+        const uint32_t m[4] = {0x00180018u, 0x00600060u, 0x01800180u, 0x06000600u};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) lc.vmask[k] = m[swap ? k ^ 2 : k];
+        lc.vs_st = !(KC && BITS == 2) && (lane & 4) ? lane ^ 1 : lane;   // lane = ((blk*4 + quad)*4 + g)*2 + half
     }
-    // Page id of list position pi and its number of valid tokens.  A page id outside its pool cannot be
-    // addressed: it is flagged, a valid page is read instead and skipped.
-    auto resolve = [&](int pi, int &page) -> int {
-        page = __builtin_amdgcn_readfirstlane(pages[pi]);
-        const bool ok = page >= page_lo && page < page_hi;
-        if (!ok) {
-            if (status && lane == 0)
-                atomicOr(status, page < 0 || page >= n_pages_total ? TKV_STATUS_PAGE_RANGE : TKV_STATUS_BITMAP_MISMATCH);
-            page = page_lo;
-        }
-        return ok ? (pi == last_index ? last_valid : kPageTokens) : 0;
-    };
     // One register set: every part of the next record is requested as soon as the registers it lands in
     // are dead, so about one page per wavefront is in flight while the current one is computed.
-    PageRegs<BITS> pr;
-    int page = 0;
-    int nv = resolve(pb, page), nv_next = 0;
-    const uint8_t *rec = pool + record_offset(page, kvh, n_kv_heads, n_pages_int2);
-    load_page_a<BITS>(pr, rec, bit_map, page, lane);
-    load_page_b<BITS>(pr, rec, lane);
+    PageRegs<BITS> &pr = s0.pr;
+    int nv = s0.nv, page_next = s0.page_next, nv_next = s0.nv_next;
     int quartile = -1;
     for (int pi = pb; pi < pe; ++pi) {
         // Wavefronts that share a SIMD are served oldest first; left alone, the oldest finishes long before
@@ -520,29 +681,32 @@ __device__ __forceinline__ void run_pages(const uint8_t *__restrict__ pool, cons
             else if (q == 1) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
-        // the last page requests its own record again: no branch around the loads
-        const int pi_next = pi + 1 < pe ? pi + 1 : pi;
-        const uint8_t *rec_next = rec;
+        // The id of the page after next is requested now, as a per-lane load (`opaque_zero`), and turned into a
+        // scalar at the end of this page: its latency never stands between two pages.  The last page requests its
+        // own record again: no branch around the loads.
+        const int pi_next2 = pi + 2 < pe ? pi + 2 : pe - 1;
+        const int pgv = pages[pi_next2 + lc.opaque_zero];
+        const uint8_t *rec_next = pool + record_offset(page_next, kvh, n_kv_heads, n_pages_int2);
+        const uint32_t bm = pr.bm;
         auto after_qk = [&]() {
             __builtin_amdgcn_sched_barrier(0);   // keep the reloads below the last use of the registers they overwrite
-            int page_next;
-            nv_next = resolve(pi_next, page_next);
-            rec_next = pool + record_offset(page_next, kvh, n_kv_heads, n_pages_int2);
-            load_page_a<BITS>(pr, rec_next, bit_map, page_next, lane);
+            load_page_meta<BITS>(pr, rec_next, bit_map, page_next, lane, lc.opaque_zero);
+            load_page_k<BITS, KC>(pr, rec_next, lane);
         };
         auto after_pv = [&]() {
             __builtin_amdgcn_sched_barrier(0);
-            load_page_b<BITS>(pr, rec_next, lane);
+            load_page_v<BITS>(pr, rec_next, lane);
         };
         // the bit_map entry arrives with the page: a mismatch skips the whole page
-        if (pr.bm != BITS && nv > 0) {
+        if (__any(bm != BITS) && nv > 0) {
             if (status && lane == 0) atomicOr(status, TKV_STATUS_BITMAP_MISMATCH);
             nv = 0;
         }
         // a page with no valid token still runs (every token masked by count): no second path through the loop
         compute_page<BITS, KC>(pr, nv, lane, qz, lc, st, lds, after_qk, after_pv);
-        rec = rec_next;
         nv = nv_next;
+        page_next = __builtin_amdgcn_readfirstlane(pgv);
+        nv_next = validate_page(cx, wr, pi_next2, page_next);
     }
 }
 
@@ -556,20 +720,26 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     float kappa, float *__restrict__ acc_ws, float *__restrict__ ml_ws, int32_t *status
     )
 {
-    using QF = typename std::conditional<KC, _Float16, float>::type;   // q * 2^E is exact in either type
+    using QF = _Float16;   // q * 2^E is exact in fp16 (q has 8 significant bits)
     __shared__ Lds<KC> lds;
-    // q * 2^E per head and channel, read while the MFMA operands are built.  The per-channel-key kernel keeps it
-    // (2 KiB of fp16) in the page staging area ks | vs | vz, which is idle then, so that twelve wavefronts
-    // still fit the LDS of a compute unit; it is written again before the INT4 operand is built.
-    __shared__ QF qf_own[KC ? 1 : 8][kHeadDim];
-    QF(*qf)[kHeadDim] = KC ? reinterpret_cast<QF(*)[kHeadDim]>(lds.ks) : qf_own;
-    static_assert(sizeof(lds.ks) + sizeof(lds.vs) + sizeof(lds.vz) >= 8 * kHeadDim * sizeof(_Float16) && sizeof(lds.ks) % 16 == 0 &&
-                  sizeof(lds.vs) % 16 == 0, "ks, vs, vz are consecutive members and together hold q for 8 heads");
+    // q * 2^E per head and channel (2 KiB of fp16), read while the MFMA operands are built: it lives in the page
+    // staging area ks | pv, which is idle then, so that twelve wavefronts fit the LDS of a compute unit; it is
+    // written again before the INT4 operand is built.
+    QF(*qf)[kHeadDim] = reinterpret_cast<QF(*)[kHeadDim]>(lds.ks);
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
     const int seq = items[4 * item];
-    if (seq < 0 || seq >= batch) return;   // malformed item: nothing is read or written for it
+    if (seq < 0 || seq >= batch) {
+        // malformed item: an empty partial (m = -inf, l = 0), which the merge ignores, and a status bit
+        for (int h = 0; h < R; ++h) {
+            const size_t ph = (size_t)item * n_q_heads + kvh * R + h;
+            reinterpret_cast<float2 *>(acc_ws + ph * kHeadDim)[lane] = make_float2(0.0f, 0.0f);
+            if (lane == 0) reinterpret_cast<float2 *>(ml_ws)[ph] = make_float2(-INFINITY, 0.0f);
+        }
+        if (status && lane == 0) atomicOr(status, TKV_STATUS_BAD_ITEM);
+        return;
+    }
     const int n2 = n_tok_int2[seq], n4 = n_tok_int4[seq];
     const int np2 = (n2 + kPageTokens - 1) / kPageTokens, np4 = (n4 + kPageTokens - 1) / kPageTokens;
     const int seq_pages = page_indptr[seq + 1] - page_indptr[seq];
@@ -577,6 +747,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     const int pb = items[4 * item + 1] > 0 ? items[4 * item + 1] : 0;
     const int pe = items[4 * item + 2] < np_all ? items[4 * item + 2] : np_all;
     const int32_t *pages = page_ids + page_indptr[seq];
+    const int n_pages_total = n_pages_int2 + n_pages_int4;
+    // INT2 pages of the range, then INT4 pages: each page runs one dequantisation path
+    const int e2 = pe < np2 ? pe : np2, b4 = pb > np2 ? pb : np2;
+    const bool has2 = pb < e2, has4 = b4 < pe;
+    int opaque_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
+    const ItemCtx cx = {pool, bit_map, pages, kvh, n_kv_heads, n_pages_int2, n_pages_total, lane, opaque_zero, status};
+    const WidthRange wr2 = {pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2};
+    const WidthRange wr4 = {b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2, n_pages_total};
+    Started<2> s2;
+    Started<4> s4;
 
     // ---- q: load the R heads, common power-of-two normalisation, group sums ----
     // lane l holds channels 2l, 2l+1 of every head
@@ -601,108 +782,124 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     LaneConst lc;
     lc.F = ldexpf(1.0f, 24 - E);
     lc.kappa = kappa;
-    lc.negk = r16 >= 8 ? -1.0f : 0.0f;
-    lc.lomask = r16 >= 8 ? 0xffffffffu : 0u;
     lc.vmul01 = lc.vmul23 = 0;
     lc.zmul = r16 >= 8 ? 0.0f : 0x1p-24f;
+    lc.vs_idx = kPvS + q4 * 4 + 2 * (r16 >> 3);
+    lc.vs_st = lane;
+    lc.opaque_zero = opaque_zero;
+    lc.vrot[0] = lc.vrot[1] = 0;
+    lc.vmask[0] = lc.vmask[1] = lc.vmask[2] = lc.vmask[3] = 0;
+    lc.tok0 = 16 * (r16 >> 3) + 4 * q4;
+    lc.qy_ent = (r16 >> 3) == (q4 >> 1) ? (q4 & 1) * 8 + (r16 & 7) : kQyZero;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        lc.zp_idx[blk] = r16 < 4 ? kPvZ + (blk * 4 + q4) * 4 + r16 : (r16 == 4 ? kPvOne : kPvZero);
+    }
+    if (lane < 2) {
+        const uint32_t c = lane == 1 ? 0x3c003c00u : 0u;
+        lds.pv[kPvZero + lane] = make_uint4(c, c, c, c);
+    }
     // q * 2^E to LDS; per-group sums of the unscaled q: lanes 16g .. 16g+15 hold group g
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
-        if constexpr (KC) reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(qv[h][0] * two_e, qv[h][1] * two_e);
-        else reinterpret_cast<float2 *>(qf[h])[lane] = make_float2(qv[h][0] * two_e, qv[h][1] * two_e);
+        reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(qv[h][0] * two_e, qv[h][1] * two_e);
         float sum = qv[h][0] + qv[h][1];
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o);
-        if (r16 == 0) lds.zl[h][q4] = sum;   // [head][group]
+        if (r16 == 0) lds.zl()[h][q4] = sum;   // [head][group]
     }
     lds_order();
     const int hcol = (r16 & 7) & (R - 1);   // head of this lane's column (columns beyond R repeat heads)
     half8 qz;
     {
-        // Z-term B operand: slots 0..3 / 4..7 of chunk 0 = hi / mid pieces of the four group sums,
-        // slots 0..3 of chunk 1 = lo pieces, everything else zero
-        const float4 gs = reinterpret_cast<const float4 *>(lds.zl[hcol])[0];
+        // Z-term B operand (two token sets: the k-slots of a column's own set carry the pieces, the others zeros):
+        // slots 0..3 / 4..7 of the first octet = hi / mid pieces of the four group sums, slots 0..3 of the second
+        // octet = lo pieces
+        const float4 gs = reinterpret_cast<const float4 *>(lds.zl()[hcol])[0];
         const float sums[4] = {gs.x, gs.y, gs.z, gs.w};
         float pc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const bool own = (r16 >> 3) == (q4 >> 1);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const _Float16 hi = (_Float16)sums[g];
             const float r1 = sums[g] - (float)hi;
             const _Float16 mid = (_Float16)r1;
             const _Float16 lo = (_Float16)(r1 - (float)mid);
-            if (q4 == 0) { pc[g] = (float)hi; pc[4 + g] = (float)mid; }
-            else if (q4 == 1) { pc[g] = (float)lo; }
+            if (own && (q4 & 1) == 0) { pc[g] = (float)hi; pc[4 + g] = (float)mid; }
+            else if (own) { pc[g] = (float)lo; }
         }
         qz = as_half8(pack_h2(pc[0], pc[1]), pack_h2(pc[2], pc[3]), pack_h2(pc[4], pc[5]), pack_h2(pc[6], pc[7]));
     }
 
     WaveState st;
 #pragma unroll
-    for (int jt = 0; jt < 8; ++jt) st.acc[jt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    st.zacc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 8; ++j) st.acc[j >> 2][j & 3] = floatx4{0.f, 0.f, 0.f, 0.f};
+    st.zp = floatx4{0.f, 0.f, 0.f, 0.f};
     st.m_ref = -INFINITY;
+    st.sat = 0;
 
-    const int n_pages_total = n_pages_int2 + n_pages_int4;
-    // INT2 pages of the range, then INT4 pages: each page runs one dequantisation path
-    const int e2 = pe < np2 ? pe : np2;
-    if (pb < e2) {
+    if (has2) {
         build_q_operand<2, KC>(qf[hcol], q4, lane, lds);
         LaneConst lc2 = lc;
         if constexpr (KC) {
             lc2.kappa = lc.kappa * lc.F;   // the power of two that the K scale carries otherwise
             lds.kc_nil()[lane & 31] = make_uint4(0u, 0u, 0u, 0u);
         }
+        start_pages<2, KC>(cx, wr2, s2);
         lds_order();
-        run_pages<2, KC>(pool, bit_map, pages, pb, e2, np2 - 1, n2 - (np2 - 1) * kPageTokens, 0, n_pages_int2,
-                         n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc2, st, lds, status);
+        run_pages<2, KC>(cx, wr2, s2, pe, pe - pb, qz, lc2, st, lds);
     }
-    const int b4 = pb > np2 ? pb : np2;
-    if (b4 < pe) {
-        if constexpr (KC) {
-            if (pb < e2) {   // the INT2 pages have used the staging area since
-                lds_order();
+    if (has4) {
+        start_pages<4, KC>(cx, wr4, s4);
+        if (has2) {   // the INT2 pages have used that memory since
+            lds_order();
 #pragma unroll
-                for (int h = 0; h < 8; ++h) {
-                    uint32_t two = 0;
-                    if (h < R) two = reinterpret_cast<const uint32_t *>(q + ((size_t)seq * n_q_heads + kvh * R + h) * kHeadDim)[lane];
-                    reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(__uint_as_float(two << 16) * two_e, __uint_as_float(two & 0xffff0000u) * two_e);
-                }
-                lds_order();
+            for (int h = 0; h < 8; ++h) {
+                uint32_t two = 0;
+                if (h < R) two = reinterpret_cast<const uint32_t *>(q + ((size_t)seq * n_q_heads + kvh * R + h) * kHeadDim)[lane];
+                const float q0 = __uint_as_float(two << 16) * two_e, q1 = __uint_as_float(two & 0xffff0000u) * two_e;
+                reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(q0, q1);
             }
+            lds_order();
         }
         build_q_operand<4, KC>(qf[hcol], q4, lane, lds);
         lds_order();
-        run_pages<4, KC>(pool, bit_map, pages, b4, pe, np2 + np4 - 1, n4 - (np4 - 1) * kPageTokens, n_pages_int2,
-                     n_pages_total, n_pages_total, kvh, n_kv_heads, n_pages_int2, pe, pe - pb, lane, qz, lc, st, lds, status);
+        run_pages<4, KC>(cx, wr4, s4, pe, pe - pb, qz, lc, st, lds);
     }
 
     // ---- write the partial (m, l, acc) of this item ------------------------------
-    // rows 0..7 carry the hi piece of P, rows 8..15 the lo piece: add lanes l and l^32
-#pragma unroll
-    for (int jt = 0; jt < 8; ++jt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) st.acc[jt][i] += __shfl_xor(st.acc[jt][i], 32);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) st.zacc[i] += __shfl_xor(st.zacc[i], 32);
+    if (status && __any(st.sat != 0) && lane == 0) atomicOr(status, TKV_STATUS_SCALE_SATURATED);
+    // per head: columns 0..3 of zl = zero-point sums of the groups, 4 = denominator
     lds_order();
-    if (r16 < 8 && q4 < 2)
+    if (q4 < 2 && r16 < 5)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lds.zl[4 * q4 + i][r16] = st.zacc[i];   // [head][column]
+        for (int i = 0; i < 4; ++i) lds.zl()[4 * q4 + i][r16] = st.zp[i];
     if (q4 == 0 && r16 < 8) lds.alpha[r16] = st.m_ref;
     lds_order();
     const float unscale = ldexpf(1.0f, 24 - kVExp);
-    if (q4 < 2) {
+    const int hb = r16 >> 3;
+    if ((q4 >> 1) == hb) {   // the quadrants whose rows and columns belong to the same pair of groups
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int head = 4 * q4 + i;
+            const int head = 4 * (q4 & 1) + i;
             if (head >= R) continue;
             const size_t ph = (size_t)item * n_q_heads + kvh * R + head;
-            float *dst = acc_ws + ph * kHeadDim;
+            float *dst = acc_ws + ph * kHeadDim + 64 * hb;
 #pragma unroll
-            for (int jt = 0; jt < 8; ++jt) dst[16 * jt + r16] = st.acc[jt][i] * unscale + lds.zl[head][jt >> 1];
-            if (r16 == 0) {
+            for (int gg = 0; gg < 2; ++gg) {
+                const int g = 2 * hb + gg;
+                const float zsum = lds.zl()[head][g];
+#pragma unroll
+                for (int chunk = 0; chunk < 2; ++chunk)
+#pragma unroll
+                    for (int cc = 0; cc < 2; ++cc) {
+                        const int comp = 2 * gg + cc;
+                        dst[16 * comp + (chunk ? r16 ^ 8 : r16)] = st.acc[chunk][comp][i] * unscale + zsum;
+                    }
+            }
+            if ((r16 & 7) == 0 && hb == 0) {
                 ml_ws[2 * ph] = lds.alpha[head];
-                ml_ws[2 * ph + 1] = lds.zl[head][4];
+                ml_ws[2 * ph + 1] = lds.zl()[head][4];
             }
         }
     }

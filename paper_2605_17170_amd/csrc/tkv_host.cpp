@@ -335,7 +335,25 @@ int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page
         if (page_indptr[b + 1] - page_indptr[b] != p2 + p4) return TKV_ERR_INVALID_ARG;
         total += kCost2 * p2 + kCost4 * p4;
     }
-    const int64_t per_item = std::max<int64_t>(1, (total + target_items - 1) / target_items);
+    // The launch ends with its slowest wavefront: find the smallest bound on an item's cost for which the batch
+    // still splits into at most target_items items (every sequence into ceil(cost / bound) equal parts), so that no
+    // item is heavier than the others by more than the rounding to whole pages.
+    auto items_for = [&](int64_t bound) {
+        int64_t n = 0;
+        for (int32_t b = 0; b < batch; ++b) {
+            const int64_t p2 = ceil_div(n_tok_int2[b], kPageTokens), p4 = ceil_div(n_tok_int4[b], kPageTokens);
+            const int64_t cost = kCost2 * p2 + kCost4 * p4;
+            if (cost > 0) n += std::min<int64_t>(p2 + p4, (cost + bound - 1) / bound);
+        }
+        return n;
+    };
+    int64_t lo = 1, hi = std::max<int64_t>(1, total);   // items_for(hi) <= number of non-empty sequences
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (items_for(mid) <= (int64_t)target_items) hi = mid;
+        else lo = mid + 1;
+    }
+    const int64_t per_item = lo;   // with more non-empty sequences than target_items: one item each
     int32_t n_items = 0;
     seq_item_indptr_out[0] = 0;
     for (int32_t b = 0; b < batch; ++b) {
@@ -343,7 +361,7 @@ int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page
         const int32_t pages = p2 + p4;
         const int64_t cost = kCost2 * p2 + kCost4 * p4;
         if (pages > 0) {
-            const int32_t n_split = (int32_t)std::min<int64_t>(pages, std::max<int64_t>(1, (cost + per_item / 2) / per_item));
+            const int32_t n_split = (int32_t)std::min<int64_t>(pages, (cost + per_item - 1) / per_item);
             if (n_items + n_split > capacity) return TKV_ERR_CAPACITY;
             int32_t begin = 0;
             int64_t cum = 0;   // cost of pages [0, begin)

@@ -27,6 +27,8 @@ TKV_STATUS_BITMAP_MISMATCH = 2
 TKV_STATUS_PAGE_RANGE = 4
 TKV_STATUS_DST_RANGE = 8
 TKV_STATUS_BLOCK_PARTIAL = 16
+TKV_STATUS_SCALE_SATURATED = 32
+TKV_STATUS_BAD_ITEM = 64
 TKV_KEYS_PER_TOKEN = 0
 TKV_KEYS_PER_CHANNEL = 1
 

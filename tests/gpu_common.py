@@ -71,12 +71,12 @@ def decode_ref(q, Kq, Vq, seq_lens):
     return orc.attention_quantized(q, Kq, Vq, ip, SM)
 
 
-def gpu_decode(cache, q, target_items):
+def gpu_decode(cache, q, target_items, expect_status=0):
     cache.plan_decode(target_items)
     dq = harness.bf16_tensor(q, DEV)
     out = cache.decode(dq)
     torch.cuda.synchronize()
-    assert int(cache.status.item()) == 0
+    assert int(cache.status.item()) == expect_status
     return out.cpu().numpy()
 
 

@@ -197,15 +197,56 @@ def test_v_magnitudes_across_the_supported_range(G):
         _run(G, q, K, Vs, seq_bits, 8, 1, targets=(1, 9))
 
 
-def test_v_scale_beyond_the_limit_saturates_and_stays_finite(G):
+def test_v_scale_beyond_the_limit_saturates_is_flagged_and_stays_finite(G):
     """Out of contract (V scale > 255): the staged scale saturates, the output is wrong but finite and
-    nothing is flagged; documents the behaviour promised in the header."""
+    TKV_STATUS_SCALE_SATURATED is raised; a cache just inside the limit raises nothing and is in tolerance."""
     q, K, V, seq_bits = G.random_case(23, [300], 8, 1)
     Vs = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(V) * np.float32(64.0))
     cache, _ = G.check_append(seq_bits, K, Vs, 1)
-    out = G.gpu_decode(cache, q, 3)
+    out = G.gpu_decode(cache, q, 3, expect_status=tkv.TKV_STATUS_SCALE_SATURATED)
     assert np.all(np.isfinite(out))
     cache.close()
+    Vs = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(V) * np.float32(4.0))      # INT2 scales of the x20 channels reach ~200
+    cache, (Kq, Vq) = G.check_append(seq_bits, K, Vs, 1)
+    assert Vq[1].view(np.float16).max() > 100
+    G.assert_close(G.gpu_decode(cache, q, 3), G.decode_ref(q, Kq, Vq, [300]), "V scales up to %.0f" % Vq[1].view(np.float16).max())
+    cache.close()
+
+
+def test_item_naming_a_sequence_outside_the_batch_is_flagged_and_contributes_nothing(G):
+    q, K, V, seq_bits = G.random_case(24, [400, 200], 8, 2)
+    cache, (Kq, Vq) = G.check_append(seq_bits, K, V, 2)
+    try:
+        ref = G.decode_ref(q, Kq, Vq, [400, 200])
+        items, sip = cache.plan_decode(6)
+        bad = items.copy()
+        k = int(sip[1]) - 1                      # the last item of sequence 0 is replaced by a malformed one
+        lost = bad[k].copy()
+        bad[k, 0] = 7
+        cache._plan = (torch.from_numpy(bad).to(G.DEV), cache._plan[1], bad, sip)
+        ws = cache.workspace(8)
+        ws.view(torch.float32).fill_(float("nan"))   # whatever an earlier call left there must not reach the output
+        out = cache.decode(harness.bf16_tensor(q, G.DEV), workspace=ws)
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == tkv.TKV_STATUS_BAD_ITEM
+        out = out.cpu().numpy()
+        assert np.all(np.isfinite(out))
+        G.assert_close(out[1:], ref[1:], "the untouched sequence")
+        # sequence 0 is attention over the pages of its remaining items: compare with the oracle on those tokens
+        from oracle import tkv_oracle as orc
+        keep = np.ones(400, bool)
+        slots = cache.slot_ids[:400].astype(np.int64)
+        pages0 = cache.page_ids[cache.page_indptr[0]:cache.page_indptr[1]]
+        dropped = set(int(p) for p in pages0[lost[1]:lost[2]])
+        for t in range(400):
+            keep[t] = int(slots[t] // 64) not in dropped
+        sel = np.nonzero(keep)[0]
+        Kq0 = tuple(a[sel] for a in Kq)
+        Vq0 = tuple(a[sel] for a in Vq)
+        ref0 = G.decode_ref(q[:1], Kq0, Vq0, [sel.size])
+        G.assert_close(out[:1], ref0, "sequence 0 without the malformed item's pages")
+    finally:
+        cache.close()
 
 
 def test_cfg1(G):

@@ -191,14 +191,14 @@ def test_decode_key_scales_across_the_supported_range(G):
         cache.close()
 
 
-def test_key_scale_beyond_the_limit_saturates_and_stays_finite(G):
+def test_key_scale_beyond_the_limit_saturates_is_flagged_and_stays_finite(G):
     """Out of contract (per-channel key scale > 1023): the staged scale saturates, the output is wrong but
-    finite and nothing is flagged; documents the behaviour promised in the header."""
+    finite and TKV_STATUS_SCALE_SATURATED is raised."""
     q, K, V, _ = G.random_case(20, [256], 8, 1)
     Ks = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(K) * np.float32(300.0))
     cache, ref = G.kc_check_append([np.full(256, 2, np.uint8)], Ks, V, 1)
     assert ref[4].view(np.float16).max() > 1023
-    out = G.gpu_decode(cache, q, 3)
+    out = G.gpu_decode(cache, q, 3, expect_status=tkv.TKV_STATUS_SCALE_SATURATED)
     assert np.all(np.isfinite(out))
     cache.close()
 
