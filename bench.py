@@ -1,24 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the TriAxialKV decode / append hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--legs all|none] [--no-cpu]
 
-Prints ONE JSON line.  A "step" is one decode-attention step of one layer over
-the whole batch of the workload: split-K decode kernel + cross-split reduction
-(tkv_decode_attention through the C ABI), reading a paged INT2/INT4 cache that
-tkv_quantize_append built from the workload's bf16 K/V before the timed
-region (that append is timed too and reported under "append").  Inputs are
-resident in HBM when timing starts.  To keep the 256 MB Infinity Cache from
-serving the pool, the steps rotate over several identical copies of the pool
-whose total size exceeds 512 MB ("cold" protocol); a warm number (one copy)
-is reported beside it.
+Prints ONE JSON line.  The headline workload is cfg5, the largest single-GPU
+configuration of the baseline file: a Llama-3-70B-shaped decode step, 80
+layers, 64 query heads on 8 kv heads, batch 32, context lengths lognormal
+between 4K and 128K tokens, tokens at INT2 or INT4 by their tag (2.6 bits on
+average).  A "step" is the decode attention of ONE generated token through
+all 80 layers: 80 x tkv_decode_attention (split-K kernel + cross-split
+reduction, through the C ABI) back to back on one stream, each layer reading
+its own paged pool (page table shared by the layers, K/V of every layer drawn
+from its own seed).  The pools (64 GB) are built before the timed region by
+tkv_quantize_append and are resident in HBM; a layer's pool (805 MB) is far
+larger than the 256 MB Infinity Cache, so every step reads from HBM.
 
 value = effective KV bytes per second = (96 B per INT2 token + 160 B per INT4
-token) x kv heads, summed over the batch, divided by the step time.
+token) x kv heads, summed over the batch and the layers, divided by the step
+time.  The other configurations of the baseline file run as legs of the same
+line (one layer each, pools rotated over copies larger than the Infinity
+Cache): cfg2, cfg3 and cfg1 decode steps, the cfg4 append.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import math
 import os
@@ -31,75 +37,187 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+METRIC = "effective KV GB/s + µs/decode step (mixed INT2/INT4), % of HBM peak"
+SHAPES = {
+    "cfg1": "cfg1 (B=1, Hq=4, Hkv=1, d=128, ctx 2048, 1 layer)",
+    "cfg2": "cfg2 (Qwen3-VL-32B-shaped layer: B=8, Hq=64, Hkv=8, d=128, ctx 32768, 1 layer)",
+    "cfg3": "cfg3 (B=4, Hq=4, Hkv=1, d=128, ctx 102400, 1 layer, pool sized for 16 sequences)",
+    "cfg5": "cfg5 (Llama-3-70B-shaped decode step: 80 layers, B=32, Hq=64, Hkv=8, d=128, ctx lognormal 4K..128K)",
+}
 
 
-def _events(n):
-    import torch
-    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+def csrc_hash() -> str:
+    """Hash of the kernel sources: ties a profile summary to the binary it was taken from."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2605_17170_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:12]
 
 
-def time_steps(fn, steps, warmup):
-    """Per-step GPU durations (ms) from HIP events on the launch stream, and
-    the wall time of the whole timed region bracketed by synchronize()."""
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary (profiles/<name>),
+    or None when there is none or it was taken from other kernel sources than the ones in the tree."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    val, sha = None, None
+    for line in open(path):
+        if line.startswith("hbm_bytes_per_launch"):
+            val = float(line.split("=")[1])
+        if line.startswith("csrc_sha"):
+            sha = line.split("=")[1].strip()
+    return val if sha == csrc_hash() else None
+
+
+def timed(fn, steps, warmup):
+    """Runs fn(i) `warmup` + `steps` times; returns (per-step ms from HIP events on the launch stream, wall ms per
+    step between two synchronisations)."""
     import torch
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
-    ev = _events(steps + 1)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     ev[0].record()
     for i in range(steps):
         fn(i)
         ev[i + 1].record()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])
-    return per, wall
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]), wall
 
 
-def cpu_baseline(w, q, K, V, max_seconds=30.0):
-    """The oracle's decode attention, timed as it stands on the host cores, on
-    a bounded sample of the same workload (whole sequences, all heads)."""
+def frac(nbytes, ms):
+    return nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+
+def cpu_baseline(w, q_host, K_host, V_host, nseq, note):
+    """The oracle's decode attention, as it stands, on the host cores, on the leading `nseq` sequences."""
     from oracle import tkv_oracle as orc
     bits = w.all_bits()
     ip = w.seq_indptr
-    # sample: as many leading sequences as ~4M tokens x kv heads allow (a few seconds of scalar work)
-    budget_tok = max(1, 4_000_000 // w.n_kv_heads)
-    nseq = 1
-    while nseq < w.batch and ip[nseq + 1] <= budget_tok:
-        nseq += 1
     T = int(ip[nseq])
-    Kq = orc.quantize(K[:T], bits[:T])
-    Vq = orc.quantize(V[:T], bits[:T])
+    Kq = orc.quantize(K_host[:T], bits[:T])
+    Vq = orc.quantize(V_host[:T], bits[:T])
     sm = float(np.float32(1.0 / math.sqrt(128.0)))
     t0 = time.perf_counter()
-    orc.attention_quantized(q[:nseq], Kq, Vq, ip[:nseq + 1], sm)
+    orc.attention_quantized(q_host[:nseq], Kq, Vq, ip[:nseq + 1], sm)
     dt = time.perf_counter() - t0
     nbytes = w.n_kv_heads * (96 * int((bits[:T] == 2).sum()) + 160 * int((bits[:T] == 4).sum()))
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "%d of %d sequences (%d tokens, all heads), decode attention only, %.2f s" % (nseq, w.batch, T, dt)}
+            "sample": "%s: %d of %d sequences (%d tokens, all heads), decode attention only, %.2f s" % (note, nseq, w.batch, T, dt),
+            "seconds": dt, "bytes": nbytes}
 
 
-def read_traffic(name):
-    """HBM bytes per launch of the dominant kernel from committed rocprofv3
-    --pmc summaries (profiles/<name>), or None."""
-    path = os.path.join(ROOT, "profiles", name)
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        if line.startswith("hbm_bytes_per_launch"):
-            return float(line.split("=")[1])
-    return None
+def decode_leg(name, steps, warmup, key_axis=0, n_layers=1):
+    """Decode step of one configuration on device-generated K/V.  n_layers > 1: one pool per layer, a step walks all
+    layers; otherwise the pool is rotated over copies whose total exceeds 768 MB (cold protocol)."""
+    import torch
+    from paper_2605_17170_amd import harness, tkv
+    from paper_2605_17170_amd import workloads as wl
+    dev = torch.device("cuda:0")
+    w = wl.config(name)
+    pool_factor = 4.0 if name == "cfg3" else 1.0
+    cache = harness.PagedCache(w.n_kv_heads, w.bits, dev, pool_factor=pool_factor, shuffle_seed=w.seed + 1, key_axis=key_axis,
+                               alloc_pool=False)
+    target = harness.default_target_items(w.n_kv_heads, dev)
+    t0 = time.perf_counter()
+    items, _ = cache.plan_decode(target)
+    plan_us = (time.perf_counter() - t0) * 1e6
+    kv_bytes = cache.kv_bytes()
+    pools, qs = [], []
+    app_ms = []
+    for layer in range(n_layers):
+        K, V = harness.device_kv(w.n_tokens, w.n_kv_heads, w.seed * 1000 + layer, dev)
+        pool = torch.empty(cache.pool_bytes, dtype=torch.uint8, device=dev)
+        if layer == 0:
+            per, _ = timed(lambda i: cache.append(K, V, pool=pool), 3, 1)
+            app_ms = float(np.median(per))
+        else:
+            cache.append(K, V, pool=pool)
+        pools.append(pool)
+        qs.append(harness.device_q(w.batch, w.n_q_heads, w.seed * 1000 + layer, dev))
+        del K, V
+    if n_layers == 1:
+        n_copies = max(1, min(8, int(math.ceil(768e6 / max(cache.pool_bytes, 1)))))
+        pools += [pools[0].clone() for _ in range(n_copies - 1)]
+        qs = qs * n_copies
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float32, device=dev)
+    ws = cache.workspace(w.n_q_heads)
+    n_pools = len(pools)
+
+    if n_layers > 1:
+        def step(i):
+            for layer in range(n_layers):
+                cache.decode(qs[layer], out=out, workspace=ws, pool=pools[layer])
+
+        def split_only(i):
+            for layer in range(n_layers):
+                cache.decode_split(qs[layer], workspace=ws, pool=pools[layer])
+    else:
+        def step(i):
+            cache.decode(qs[i % n_pools], out=out, workspace=ws, pool=pools[i % n_pools])
+
+        def split_only(i):
+            cache.decode_split(qs[i % n_pools], workspace=ws, pool=pools[i % n_pools])
+
+    per, wall_ms = timed(step, steps, warmup)
+    sp, sp_wall = timed(split_only, steps, warmup)
+    assert int(cache.status.item()) == 0
+    launches = n_layers
+    res = {
+        "workload": SHAPES[name], "n_layers": n_layers, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+        "tokens": w.n_tokens, "int4_token_share": float((cache.tag_bits == 4).mean()),
+        "kv_bytes_per_layer": kv_bytes, "kv_bytes_per_step": kv_bytes * n_layers,
+        "work_items": int(items.shape[0]), "work_items_target": int(target), "pools": n_pools,
+        "ms_per_step": wall_ms, "us_per_layer": wall_ms * 1e3 / n_layers,
+        "GBps": kv_bytes * n_layers / (wall_ms * 1e-3) / 1e9, "frac_of_hbm_peak": frac(kv_bytes * n_layers, wall_ms),
+        "kernel_us": float(np.mean(sp)) * 1e3 / launches, "kernel_frac_of_hbm_peak": frac(kv_bytes * n_layers, float(np.mean(sp))),
+        "plan_decode_host_us": plan_us,
+        "append_whole_context_ms": app_ms,
+    }
+    return res, (w, cache, pools, qs, out, ws)
+
+
+def append_leg(name, steps=5, warmup=2):
+    """tkv_quantize_append (and the prefill gather back) of a whole workload: tokens/s and read + written GB/s."""
+    import torch
+    from paper_2605_17170_amd import harness
+    from paper_2605_17170_amd import workloads as wl
+    dev = torch.device("cuda:0")
+    w = wl.config(name)
+    cache = harness.PagedCache(w.n_kv_heads, w.bits, dev, pool_factor=2.0 if name == "cfg4" else 1.0, shuffle_seed=w.seed + 1)
+    K, V = harness.device_kv(w.n_tokens, w.n_kv_heads, w.seed * 1000, dev)
+    per, _ = timed(lambda i: cache.append(K, V), steps, warmup)
+    ms = float(np.median(per))
+    rd, wr = 2 * K.numel() * 2, cache.kv_bytes()
+    gK = torch.empty((w.n_tokens, w.n_kv_heads, 128), dtype=torch.float16, device=dev)
+    gV = torch.empty_like(gK)
+    gper, _ = timed(lambda i: cache.gather(gK, gV), steps, warmup)
+    gms = float(np.median(gper))
+    assert int(cache.status.item()) == 0
+    res = {"workload": "%s: %d new bf16 K and V tokens, %d kv heads, INT4 token share %.2f, randomly allocated pages"
+                       % (name, w.n_tokens, w.n_kv_heads, w.f4()),
+           "append_ms": ms, "tokens_per_s": w.n_tokens / (ms * 1e-3), "GBps_read_plus_write": (rd + wr) / (ms * 1e-3) / 1e9,
+           "frac_of_hbm_peak": frac(rd + wr, ms), "bytes_read": rd, "bytes_written": wr,
+           "prefill_gather_ms": gms, "prefill_gather_GBps_read_plus_write": (wr + 2 * gK.numel() * 2) / (gms * 1e-3) / 1e9,
+           "prefill_gather_frac_of_hbm_peak": frac(wr + 2 * gK.numel() * 2, gms)}
+    cache.close()
+    return res
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink context lengths (debug only; makes the line invalid)")
-    ap.add_argument("--target-items", type=int, default=0)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 20 for cfg5, 200 otherwise)")
+    ap.add_argument("--warmup", type=int, default=0, help="warm-up steps (default: 3 for cfg5, 20 otherwise)")
+    ap.add_argument("--config", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg5"], help="headline workload")
+    ap.add_argument("--legs", default="all", choices=["all", "none"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -109,150 +227,104 @@ def main():
 
     import torch
     from paper_2605_17170_amd import harness, tkv
-    from paper_2605_17170_amd import workloads as wl
 
     tkv.lib()   # fail loudly if the HIP library is missing
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    w = wl.config(args.config, args.scale)
-    q, K, V, _ = w.make_inputs()
-    pool_factor = 4.0 if args.config == "cfg3" else 1.0
-    cache = harness.PagedCache(w.n_kv_heads, w.bits, dev, pool_factor=pool_factor, shuffle_seed=w.seed + 1)
-    dK, dV, dq = harness.bf16_tensor(K, dev), harness.bf16_tensor(V, dev), harness.bf16_tensor(q, dev)
+    torch.cuda.set_device(0)
+    head = args.config
+    steps = args.steps or (20 if head == "cfg5" else 200)
+    warmup = args.warmup or (3 if head == "cfg5" else 20)
+    n_layers = 80 if head == "cfg5" else 1
+    main_res, (w, cache, pools, qs, out, ws) = decode_leg(head, steps, warmup, n_layers=n_layers)
 
-    # ---- append leg (builds the cache the decode steps read)
-    app_per, _ = time_steps(lambda i: cache.append(dK, dV), 5, 2)
-    app_ms = float(np.median(app_per))
-    app_read = 2 * K.size * 2
-    app_write = cache.kv_bytes()
-    assert int(cache.status.item()) == 0
-
-    # ---- prefill gather leg (dequantises the whole cached context back into fp16 rows)
-    gK = torch.empty((w.n_tokens, w.n_kv_heads, 128), dtype=torch.float16, device=dev)
-    gV = torch.empty_like(gK)
-    gat_per, _ = time_steps(lambda i: cache.gather(gK, gV), 5, 2)
-    gat_ms = float(np.median(gat_per))
-    gat_bytes = cache.kv_bytes() + 2 * gK.numel() * 2
-    assert int(cache.status.item()) == 0
-    del gK, gV
-
-    # ---- decode leg
-    target = args.target_items or harness.default_target_items(w.n_kv_heads, dev)
-    t0 = time.perf_counter()
-    items, _ = cache.plan_decode(target)
-    plan_us = (time.perf_counter() - t0) * 1e6
-    kv_bytes = cache.kv_bytes()
-    pool_bytes = cache.pool.numel()
-    n_copies = max(1, min(8, int(math.ceil(768e6 / max(pool_bytes, 1)))))
-    pools = [cache.pool] + [cache.pool.clone() for _ in range(n_copies - 1)]
-    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float32, device=dev)
-    ws = cache.workspace(w.n_q_heads)
-
-    def step_cold(i):
-        cache.decode(dq, out=out, workspace=ws, pool=pools[i % n_copies])
-
-    def step_warm(i):
-        cache.decode(dq, out=out, workspace=ws, pool=pools[0])
-
-    def split_cold(i):
-        cache.decode_split(dq, workspace=ws, pool=pools[i % n_copies])
-
-    per, wall = time_steps(step_cold, args.steps, args.warmup)
-    ms_per_step = wall * 1e3 / args.steps
-    # the dominant kernel by itself (tkv_decode_kernel = the split launch), same rotation, HIP events per launch
-    split_per, _ = time_steps(split_cold, args.steps, args.warmup)
-    ev_ms = float(np.mean(split_per))
-    warm_per, _ = time_steps(step_warm, min(args.steps, 50), 5)
-    # speed-of-light probe: a plain 128-bit streaming read of the same pool copies, same rotation
-    probe_per, _ = time_steps(lambda i: tkv.tkv_probe_stream_read(pools[i % n_copies]), 40, 5)
-    stream_read = pool_bytes / (float(np.mean(probe_per)) * 1e-3) / 1e9
-    assert int(cache.status.item()) == 0
-    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
-
+    # speed-of-light probe: a plain 128-bit streaming read of the same pools, same order
+    probe, _ = timed(lambda i: tkv.tkv_probe_stream_read(pools[i % len(pools)]), 40, 5)
+    stream_read = cache.pool_bytes / (float(np.mean(probe)) * 1e-3) / 1e9
+    kv_layer, kv_step = main_res["kv_bytes_per_layer"], main_res["kv_bytes_per_step"]
+    kernel_us = main_res["kernel_us"]
     res = {
-        "metric": "effective KV GB/s + \u00b5s/decode step (mixed INT2/INT4), % of HBM peak",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "us_per_decode_step": ms_per_step * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u2/u4 codes, f16 MFMA operands, f32 accumulate",
-        "data": "synthetic",
-        "config": {"workload": args.config + (" (Qwen3-VL-32B-shaped layer: B=8, Hq=64, Hkv=8, d=128, ctx 32768)"
-                                              if args.config == "cfg2" else ""),
-                   "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "tokens": w.n_tokens, "int4_token_share": w.f4(), "kv_bytes_per_step": kv_bytes,
-                   "work_items": int(items.shape[0]), "pool_copies_rotated": n_copies, "scale": args.scale},
-        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
-        "warm_cache": {"us_per_step": float(np.median(warm_per)) * 1e3,
-                       "GBps": kv_bytes / (float(np.median(warm_per)) * 1e-3) / 1e9,
-                       "note": "single pool copy; may be served by the 256 MB Infinity Cache"},
-        "plan_decode_host_us": plan_us,
-        "append": {"ms": app_ms, "tokens_per_s": w.n_tokens / (app_ms * 1e-3),
-                   "GBps_read_plus_write": (app_read + app_write) / (app_ms * 1e-3) / 1e9,
-                   "pct_of_hbm_peak": 100.0 * (app_read + app_write) / (app_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                   "note": "tkv_quantize_append of the whole context (bf16 K,V read + packed pages written), outside the timed steps"},
-        "prefill_gather": {"ms": gat_ms, "tokens_per_s": w.n_tokens / (gat_ms * 1e-3),
-                           "GBps_read_plus_write": gat_bytes / (gat_ms * 1e-3) / 1e9,
-                           "pct_of_hbm_peak": 100.0 * gat_bytes / (gat_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                           "note": "tkv_gather_dequant of the whole context (packed pages read + fp16 K,V rows written), outside the timed steps"},
-        "roofline": {"bound": "hbm", "achieved": kv_bytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": kv_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": read_traffic("decode_%s_hbm_traffic.txt" % args.config),
-                     "kernel": "tkv_decode_kernel", "kernel_us": ev_ms * 1e3,
-                     "stream_read_GBps": stream_read, "frac_of_stream_read": kv_bytes / (ev_ms * 1e-3) / 1e9 / stream_read,
-                     "note": "tkv_decode_kernel launched by itself (tkv_decode_split), mean of HIP-event intervals "
-                             "between back-to-back launches; algorithmic bytes = 96 B/INT2 token + 160 B/INT4 token "
-                             "per kv head; traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE; "
-                             "stream_read_GBps = a plain 128-bit streaming read of the same pool copies (tkv_probe_stream_read), "
-                             "what the memory system delivers to a read-only scan on this box"},
+        "metric": METRIC, "value": main_res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": main_res["ms_per_step"], "us_per_decode_step": main_res["ms_per_step"] * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u2/u4 codes, f16 MFMA operands, f32 accumulate", "data": "synthetic",
+        "config": {k: main_res[k] for k in ("workload", "n_layers", "batch", "n_q_heads", "n_kv_heads", "tokens", "int4_token_share",
+                                            "kv_bytes_per_layer", "kv_bytes_per_step", "work_items", "work_items_target", "pools")},
+        "pct_of_hbm_peak": 100.0 * main_res["frac_of_hbm_peak"],
+        "us_per_layer": main_res["us_per_layer"],
+        "plan_decode": {"host_us": main_res["plan_decode_host_us"],
+                        "note": "tkv_plan_decode on the host, once: the plan stays valid until a sequence gains a page (every 64 decoded "
+                                "tokens per sequence at most) and is shared by the 80 layers, so it costs host_us / (64 x 80) per layer step"},
+        "roofline": {"bound": "hbm", "achieved": kv_layer / (kernel_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": kv_layer / (kernel_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": read_traffic("decode_%s_hbm_traffic.txt" % head),
+                     "kernel": "tkv_decode_kernel", "kernel_us": kernel_us, "bytes_per_launch": kv_layer,
+                     "stream_read_GBps": stream_read, "frac_of_stream_read": kv_layer / (kernel_us * 1e-6) / 1e9 / stream_read,
+                     "csrc_sha": csrc_hash(),
+                     "note": "tkv_decode_kernel launched by itself (tkv_decode_split) over the same pools in the same order, mean "
+                             "interval per launch from HIP events around the timed launches on the launch stream; algorithmic bytes "
+                             "per launch = 96 B/INT2 token + 160 B/INT4 token per kv head of one layer; traffic = HBM bytes per launch "
+                             "from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), null unless that summary was taken from these kernel "
+                             "sources; stream_read_GBps = a plain 128-bit streaming read of the same pools (tkv_probe_stream_read)"},
     }
-    # ---- the same workload with the paper's own INT2 key scheme (keys per channel over 32-token blocks,
-    #      tokens that do not fill a block stored at INT4): append, gather and decode legs
-    del pools
-    cache.close()
-    kc = harness.PagedCache(w.n_kv_heads, w.bits, dev, pool_factor=pool_factor, shuffle_seed=w.seed + 1,
-                            key_axis=tkv.TKV_KEYS_PER_CHANNEL)
-    kc_app, _ = time_steps(lambda i: kc.append(dK, dV), 5, 2)
-    gK = torch.empty((w.n_tokens, w.n_kv_heads, 128), dtype=torch.float16, device=dev)
-    gV = torch.empty_like(gK)
-    kc_gat, _ = time_steps(lambda i: kc.gather(gK, gV), 5, 2)
-    del gK, gV
-    kc.plan_decode(target)
-    kc_pools = [kc.pool] + [kc.pool.clone() for _ in range(n_copies - 1)]
-    kc_ws = kc.workspace(w.n_q_heads)
-    _, kc_wall = time_steps(lambda i: kc.decode(dq, out=out, workspace=kc_ws, pool=kc_pools[i % n_copies]),
-                            args.steps, args.warmup)
-    kc_split, _ = time_steps(lambda i: kc.decode_split(dq, workspace=kc_ws, pool=kc_pools[i % n_copies]),
-                             args.steps, args.warmup)
-    assert int(kc.status.item()) == 0
-    kc_bytes = kc.kv_bytes()
-    kc_ms = kc_wall * 1e3 / args.steps
-    res["per_channel_int2_keys"] = {
-        "us_per_decode_step": kc_ms * 1e3, "GBps": kc_bytes / (kc_ms * 1e-3) / 1e9,
-        "pct_of_hbm_peak": 100.0 * kc_bytes / (kc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "kernel_us": float(np.mean(kc_split)) * 1e3,
-        "kernel_frac_of_hbm_peak": kc_bytes / (float(np.mean(kc_split)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "kv_bytes_per_step": kc_bytes, "int4_token_share": float((kc.tag_bits == 4).mean()),
-        "append_ms": float(np.median(kc_app)), "prefill_gather_ms": float(np.median(kc_gat)),
-        "note": "same workload, tkv_desc.int2_key_axis = per channel; same cold-pool protocol"}
-    # ---- decode-phase append: one generated token per sequence written at INT4 into the open page
-    small = harness.PagedCache(w.n_kv_heads, [np.full(100, 4, np.uint8)] * w.batch, dev, pool_factor=2.0)
-    t0 = time.perf_counter()
-    plans = [tkv.tkv_plan_append(small.alloc, s, np.uint8([4]), b) for b, s in enumerate(small.seqs)]
-    plan1_us = (time.perf_counter() - t0) * 1e6
-    wp1 = torch.from_numpy(np.concatenate([p[1] for p in plans])).to(dev)
-    ws1 = torch.from_numpy(np.concatenate([p[2] for p in plans])).to(dev)
-    b1 = torch.full((w.batch,), 4, dtype=torch.uint8, device=dev)
-    one_per, _ = time_steps(lambda i: tkv.tkv_quantize_append(small.desc, small.pool, small.bit_map, dK[:w.batch], dV[:w.batch],
-                                                              b1, wp1, ws1, small.status), 50, 5)
-    assert int(small.status.item()) == 0
-    res["decode_phase_append"] = {"us_per_step": float(np.median(one_per)) * 1e3, "plan_host_us": plan1_us,
-                                  "note": "tkv_quantize_append of one new INT4 token per sequence (%d sequences, %d kv heads), "
-                                          "interval between back-to-back launches through the Python binding (bounded below by the host's call "
-                                          "overhead; the kernel's own duration is in the rocprofv3 kernel trace); host planning of the %d "
-                                          "single-token appends beside it"
-                                          % (w.batch, w.n_kv_heads, w.batch)}
-    small.close()
     if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(w, q, K, V)
+        # the oracle on a bounded sample: the leading sequences of layer 0 (device-generated K/V copied to the host)
+        budget_tok = max(1, 4_000_000 // w.n_kv_heads)
+        ip = w.seq_indptr
+        nseq = 1
+        while nseq < w.batch and ip[nseq + 1] <= budget_tok:
+            nseq += 1
+        T = int(ip[nseq])
+        K, V = harness.device_kv(w.n_tokens, w.n_kv_heads, w.seed * 1000, torch.device("cuda:0"))
+        Kh = K[:T].view(torch.int16).cpu().numpy().view(np.uint16)
+        Vh = V[:T].view(torch.int16).cpu().numpy().view(np.uint16)
+        qh = qs[0][:nseq].view(torch.int16).cpu().numpy().view(np.uint16)
+        del K, V
+        cb = cpu_baseline(w, qh, Kh, Vh, nseq, "layer 0 of %s" % head)
+        if n_layers > 1:
+            cb["extrapolated_seconds_per_step"] = cb["seconds"] * kv_step / cb["bytes"]
+            cb["sample"] += "; extrapolated to the whole step (all sequences, %d layers) by bytes" % n_layers
+        res["cpu_baseline"] = cb
+    del pools, qs
+    cache.close()
+    torch.cuda.empty_cache()
+
+    if args.legs == "all":
+        legs = {}
+        for name in ("cfg2", "cfg3", "cfg1"):
+            if name == head:
+                continue
+            r, keep = decode_leg(name, 200, 20)
+            keep[1].close()
+            del keep
+            torch.cuda.empty_cache()
+            legs[name + "_decode"] = r
+        r, keep = decode_leg("cfg2", 200, 20, key_axis=tkv.TKV_KEYS_PER_CHANNEL)
+        keep[1].close()
+        del keep
+        torch.cuda.empty_cache()
+        r["workload"] += ", INT2 keys quantised per channel over 32-token blocks (tkv_desc.int2_key_axis)"
+        legs["cfg2_decode_per_channel_int2_keys"] = r
+        legs["cfg4_append"] = append_leg("cfg4")
+        legs["cfg2_append"] = append_leg("cfg2")
+        # decode-phase append: one generated token per sequence written at INT4 into the open page
+        import torch as _t
+        dev = _t.device("cuda:0")
+        B, H = 32, 8
+        small = harness.PagedCache(H, [np.full(100, 4, np.uint8)] * B, dev, pool_factor=2.0)
+        t0 = time.perf_counter()
+        plans = [tkv.tkv_plan_append(small.alloc, s, np.uint8([4]), b) for b, s in enumerate(small.seqs)]
+        plan1_us = (time.perf_counter() - t0) * 1e6
+        wp1 = _t.from_numpy(np.concatenate([p[1] for p in plans])).to(dev)
+        ws1 = _t.from_numpy(np.concatenate([p[2] for p in plans])).to(dev)
+        b1 = _t.full((B,), 4, dtype=_t.uint8, device=dev)
+        K1, V1 = harness.device_kv(B, H, 5, dev)
+        one, _ = timed(lambda i: tkv.tkv_quantize_append(small.desc, small.pool, small.bit_map, K1, V1, b1, wp1, ws1, small.status), 50, 5)
+        assert int(small.status.item()) == 0
+        legs["decode_phase_append"] = {"us_per_step": float(np.median(one)) * 1e3, "plan_host_us": plan1_us,
+                                       "note": "tkv_quantize_append of one new INT4 token per sequence (%d sequences, %d kv heads): interval "
+                                               "between back-to-back launches through the Python binding (bounded below by the host's "
+                                               "call overhead; the kernel's own duration is in the rocprofv3 kernel trace)" % (B, H)}
+        small.close()
+        res["legs"] = legs
     print(json.dumps(res))
 
 

@@ -21,11 +21,40 @@ def bf16_tensor(bits_u16: np.ndarray, device) -> torch.Tensor:
     return t.to(device).view(torch.bfloat16)
 
 
+def device_kv(n_tokens: int, n_kv_heads: int, seed: int, device, outlier_channels: int = 4, outlier_scale: float = 20.0,
+              chunk_tokens: int = 1 << 17):
+    """Seeded synthetic K, V bf16 [T, Hkv, 128] generated on the device (input generation only, for runs that are
+    timed but not compared with the oracle): N(0,1), `outlier_channels` channels per kv head (seeded choice, fixed
+    across tokens) scaled by `outlier_scale`, as workloads.make_kv does on the host."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 31337]))
+    mult = np.ones((n_kv_heads, tkv.HEAD_DIM), np.float32)
+    for h in range(n_kv_heads):
+        mult[h, rng.choice(tkv.HEAD_DIM, outlier_channels, replace=False)] = outlier_scale
+    mult = torch.from_numpy(mult).to(device)
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & 0x7FFFFFFF)
+    out = []
+    for _ in range(2):
+        t = torch.empty((n_tokens, n_kv_heads, tkv.HEAD_DIM), dtype=torch.bfloat16, device=device)
+        for a in range(0, n_tokens, chunk_tokens):
+            b = min(n_tokens, a + chunk_tokens)
+            x = torch.randn((b - a, n_kv_heads, tkv.HEAD_DIM), dtype=torch.float32, device=device, generator=g)
+            t[a:b] = (x * mult).to(torch.bfloat16)
+        out.append(t)
+    return out[0], out[1]
+
+
+def device_q(batch: int, n_q_heads: int, seed: int, device):
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 7919 + 13) & 0x7FFFFFFF)
+    return torch.randn((batch, n_q_heads, tkv.HEAD_DIM), dtype=torch.float32, device=device, generator=g).to(torch.bfloat16)
+
+
 class PagedCache:
     """Pool + page tables of one layer for a batch of sequences."""
 
     def __init__(self, n_kv_heads: int, seq_bits: list, device, pool_factor: float = 1.0, shuffle_seed: int = 1,
-                 fill: int | None = None, key_axis: int = tkv.TKV_KEYS_PER_TOKEN):
+                 fill: int | None = None, key_axis: int = tkv.TKV_KEYS_PER_TOKEN, alloc_pool: bool = True):
         self.device = torch.device(device)
         self.n_kv_heads = n_kv_heads
         self.seq_bits = [np.ascontiguousarray(b, np.uint8) for b in seq_bits]
@@ -40,7 +69,10 @@ class PagedCache:
         self.alloc = tkv.tkv_alloc_create(self.desc, shuffle_seed)
         self.seqs = [tkv.tkv_seq_create() for _ in self.seq_bits]
         nbytes = tkv.tkv_pool_bytes(self.desc)
-        if fill is None:
+        self.pool_bytes = nbytes
+        if not alloc_pool:
+            self.pool = None      # the caller passes a pool to every call (one pool per layer)
+        elif fill is None:
             self.pool = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         else:
             self.pool = torch.full((nbytes,), fill, dtype=torch.uint8, device=self.device)

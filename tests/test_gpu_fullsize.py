@@ -1,8 +1,8 @@
 """Parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times (default work-item count): every pool byte
 against the oracle-packed pool, and every decode output against the oracle's
-fp64 attention.  cfg5 (80 layers) is checked on its last layer at full shape;
-its other layers differ only by their seed."""
+fp64 attention.  cfg5 (80 layers) is checked on its first, middle and last
+layer at full shape; the layers differ only by their seed."""
 import time
 
 import numpy as np
@@ -55,5 +55,6 @@ def test_cfg3_full_scattered_pool(G):
     _full(G, "cfg3", pool_factor=4.0)      # pool sized for 16 sequences, 4 in use, pages scattered
 
 
-def test_cfg5_last_layer_full(G):
-    _full(G, "cfg5", layer=79)
+@pytest.mark.parametrize("layer", [0, 39, 79])
+def test_cfg5_layer_full(G, layer):
+    _full(G, "cfg5", layer=layer)
