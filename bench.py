@@ -145,6 +145,10 @@ def decode_leg(name, steps, warmup, key_axis=0, n_layers=1):
         n_copies = max(1, min(8, int(math.ceil(768e6 / max(cache.pool_bytes, 1)))))
         pools += [pools[0].clone() for _ in range(n_copies - 1)]
         qs = qs * n_copies
+    else:
+        # one plain device copy of known size (a pool): the calibration point of the rocprofv3 byte counters
+        calib = pools[0].clone()
+        del calib
     torch.cuda.synchronize()
     assert int(cache.status.item()) == 0
     out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float32, device=dev)

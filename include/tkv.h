@@ -91,9 +91,13 @@ enum { TKV_KEYS_PER_TOKEN = 0, TKV_KEYS_PER_CHANNEL = 1 };
 /* Bytes of one (page, kv head) record: 6144 for bits = 2, 10240 for bits = 4, 0 otherwise
  * (codes of K and V plus fp16 scale and zero-point per group of 32 channels, Sec. 3.2.1). */
 size_t tkv_record_bytes(int bits);
-/* Bytes of one page (all kv heads), or 0 on a bad descriptor / width. */
+/* Bytes of one page of the INT2 (bits = 2) or INT4 (bits = 4) pool: n_kv_heads records, the unit the per-pool
+ * allocators hand out (Sec. 3.2.2, "Memory allocation").  0 on a bad descriptor or width; host only. */
 size_t tkv_page_bytes(const tkv_desc *desc, int bits);
-/* Bytes of the whole pool; the caller allocates this much device memory, 256-byte aligned. */
+/* Bytes of the mixed-precision pool: the INT2 pages followed by the INT4 pages in ONE buffer, so that a page id
+ * below n_pages_int2 is an INT2 page and any other an INT4 page (Sec. 3.2.2, "Shared address space": the split
+ * point is fixed when the pool is sized from the average bitwidth).  The caller allocates this much device
+ * memory, 256-byte aligned, and owns it.  0 on a bad descriptor; host only. */
 size_t tkv_pool_bytes(const tkv_desc *desc);
 /* Byte offset of the record of (page, head) inside the pool, or (size_t)-1 if out of range. */
 size_t tkv_record_offset(const tkv_desc *desc, int32_t page, int32_t head);
@@ -287,11 +291,20 @@ int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bi
 /* D1: cut page lists into work items (host).                           */
 /* ------------------------------------------------------------------ */
 /*
- * The decode kernel follows the flash-decoding design: the KV of a sequence
- * is processed as parallel contiguous splits merged by log-sum-exp
- * (Sec. 3.2.3, "Decode").  A work item is a contiguous range of one
- * sequence's page list (INT2 pages first).  Items are balanced by decode cost:
- * an INT2 page weighs 6, an INT4 page 7 (measured kernel time per page).
+ * Split-K over a sequence's page list (Sec. 3.2.3, "Decode"): a work item is a
+ * contiguous range of one sequence's page list (INT2 pages first); one
+ * wavefront per (item, kv head) leaves a partial (m, l, acc) that
+ * tkv_decode_reduce merges.  Items are balanced by decode cost (an INT2 page
+ * weighs 6, an INT4 page 7): the planner finds the smallest bound on an item's
+ * cost for which the batch still splits into at most target_items items and
+ * cuts every sequence into equal parts below that bound, so the number of items
+ * never exceeds target_items unless there are more non-empty sequences than
+ * that (then one item each).
+ * A plan depends only on the page COUNTS of the sequences: it stays valid while
+ * tokens are appended to open pages (the kernel reads the token counts from the
+ * device arrays and masks by them) and must be made again when a sequence gains
+ * a page -- at most every 64 decoded tokens per sequence.  With a stale plan the
+ * new page is simply not read.  Layers that share a page table share the plan.
  *   page_indptr   host i32[batch+1], page-list offsets of the sequences
  *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial;
  *                 with TKV_KEYS_PER_CHANNEL n_tok_int2 must be a multiple of 32)
@@ -311,12 +324,17 @@ int32_t tkv_plan_decode(const tkv_desc *desc, int32_t batch, const int32_t *page
 /* ------------------------------------------------------------------ */
 /* D2-D7: decode attention (device).                                    */
 /* ------------------------------------------------------------------ */
-/* Bytes of workspace for n_items items: fp32 (m, l, acc[head_dim]) per item and query head. */
+/* Bytes of workspace that decode attention over n_items work items needs: the partial (m, l, acc[head_dim]) in
+ * fp32 of every (item, query head), which the split kernel writes and the cross-split merge reads (Sec. 3.2.3,
+ * "Decode": splits merged by log-sum-exp).  Device memory, 16-byte aligned, owned by the caller; it needs no
+ * initialisation and may be shared by calls on the same stream.  0 on a bad descriptor or count; host only. */
 size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t n_q_heads);
 /*
+ * Decode attention over the mixed-precision paged cache (Sec. 3.2.3, "Decode"):
  * out[b, h, :] = softmax(sm_scale * q[b, h, :] . K^T) V over the dequantised
  * tokens of sequence b's pages, query head h reading kv head
- * h / (n_q_heads / n_kv_heads).  A sequence with no tokens gives zeros.
+ * h / (n_q_heads / n_kv_heads); every page runs the dequantisation path of its
+ * pool (INT2 or INT4).  A sequence with no tokens gives zeros.
  *   pool, bit_map  device, as filled by tkv_quantize_append
  *   q              device bf16 [batch, n_q_heads, head_dim]
  *   page_indptr    device i32[batch+1]
@@ -326,12 +344,18 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
  *   out            device fp32 [batch, n_q_heads, head_dim]
  *   workspace      device, >= tkv_decode_workspace_bytes(...), 16-byte aligned
  *   status         device i32, may be NULL
- * Preconditions on the cache contents (not checked): stored scales and zeros
- * finite; V scales up to 255 are used exactly, larger ones saturate at 255
- * (the kernel forms softmax weight x V scale in fp16 and keeps it finite);
- * with TKV_KEYS_PER_CHANNEL the scales of the INT2 keys likewise up to 1023
- * (the kernel forms q x K scale in fp16), and every n_tok_int2 is a multiple
- * of 32.
+ *   items          every item must name a sequence of the batch; one that does
+ *                  not contributes nothing and raises TKV_STATUS_BAD_ITEM.  The
+ *                  page range of an item is clamped to the sequence's pages.
+ * The page tables on the device must describe the same sequences as the host
+ * arrays the plan was made from (tkv_plan_decode above says when a plan ages).
+ * Preconditions on the cache contents: stored scales and zeros finite; V scales
+ * up to 255 are used exactly, larger ones are clamped there (the kernel forms
+ * softmax weight x V scale in fp16 and keeps it finite); with
+ * TKV_KEYS_PER_CHANNEL the scales of the INT2 keys likewise up to 1023 (the
+ * kernel forms q x K scale in fp16), and every n_tok_int2 is a multiple of 32.
+ * A clamped scale raises TKV_STATUS_SCALE_SATURATED: the output is then finite
+ * but not the attention over the stored values.
  * n_q_heads / n_kv_heads must be 1, 2, 4 or 8.  Two launches on `stream`:
  * the split kernel, then the cross-split reduction.
  */

@@ -960,6 +960,66 @@ __global__ __launch_bounds__(kReduceThreads) void tkv_reduce_kernel(
     }
 }
 
+
+// D7 for sequences with tens of items at most: one workgroup of four wavefronts per (sequence, query head).  A
+// half wavefront owns an item at a time: 32 lanes x 16 bytes are the item's 128 accumulators, so every partial is
+// read once with 128-bit loads and eight items are in flight per workgroup round.  Each half wavefront keeps a
+// running (M, l, acc) and the eight of them are merged through LDS.
+constexpr int kRowsThreads = 256;
+__global__ __launch_bounds__(kRowsThreads) void tkv_reduce_rows_kernel(
+    const float *__restrict__ acc_ws, const float *__restrict__ ml_ws, const int32_t *__restrict__ seq_item_indptr,
+    int n_q_heads, float *__restrict__ out)
+{
+    constexpr int kHalves = kRowsThreads / 32;   // 8
+    __shared__ float4 num_s[kHalves][32];
+    __shared__ float2 ml_s[kHalves];
+    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, tid = threadIdx.x;
+    const int half = tid >> 5, cq = tid & 31;
+    const int i0 = seq_item_indptr[b], i1 = seq_item_indptr[b + 1];
+    float M = -INFINITY, den = 0.0f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int i = i0 + half; i < i1; i += kHalves) {
+        const size_t ph = (size_t)i * n_q_heads + h;
+        const float2 ml = reinterpret_cast<const float2 *>(ml_ws)[ph];
+        const float4 a = reinterpret_cast<const float4 *>(acc_ws + ph * kHeadDim)[cq];
+        if (ml.x == -INFINITY) continue;   // an item without tokens
+        const float Mn = fmaxf(M, ml.x);
+        const float so = __builtin_amdgcn_exp2f(M - Mn), sn = __builtin_amdgcn_exp2f(ml.x - Mn);   // exp2(-inf) = 0 the first time
+        den = den * so + sn * ml.y;
+        num.x = num.x * so + sn * a.x;
+        num.y = num.y * so + sn * a.y;
+        num.z = num.z * so + sn * a.z;
+        num.w = num.w * so + sn * a.w;
+        M = Mn;
+    }
+    num_s[half][cq] = num;
+    if (cq == 0) ml_s[half] = make_float2(M, den);
+    __syncthreads();
+    if (tid < 32) {
+        float Mg = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < kHalves; ++k) Mg = fmaxf(Mg, ml_s[k].x);
+        float4 n = make_float4(0.f, 0.f, 0.f, 0.f);
+        float d = 0.0f;
+        if (Mg != -INFINITY) {
+#pragma unroll
+            for (int k = 0; k < kHalves; ++k) {
+                const float2 ml = ml_s[k];
+                const float wk = ml.x == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(ml.x - Mg);
+                const float4 a = num_s[k][tid];
+                d += wk * ml.y;
+                n.x += wk * a.x;
+                n.y += wk * a.y;
+                n.z += wk * a.z;
+                n.w += wk * a.w;
+            }
+        }
+        const float r = d > 0.0f ? 1.0f / d : 0.0f;
+        reinterpret_cast<float4 *>(out + ((size_t)b * n_q_heads + h) * kHeadDim)[tid] = make_float4(n.x * r, n.y * r, n.z * r, n.w * r);
+    }
+}
+
 } // namespace
 
 int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
@@ -987,7 +1047,10 @@ int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indpt
     const float *acc_ws = (const float *)workspace;
     const float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     // the item counts are on the device; the average per sequence picks the shape of the reduction
-    if ((int64_t)n_items > 128 * (int64_t)batch)
+    if ((int64_t)n_items <= 64 * (int64_t)batch)
+        hipLaunchKernelGGL(tkv_reduce_rows_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kRowsThreads), 0,
+                           (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
+    else if ((int64_t)n_items > 128 * (int64_t)batch)
         hipLaunchKernelGGL(tkv_reduce_kernel<16>, dim3((unsigned)(batch * n_q_heads * (kHeadDim / 16))), dim3(kReduceThreads), 0,
                            (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     else
