@@ -5,40 +5,43 @@
 // One wavefront owns one (work item, kv head): a contiguous range of one
 // sequence's page list.  All query heads that share the kv head (up to 8)
 // are processed together so the packed KV bytes are read from HBM once; the
-// partials (m, l, acc) of the items are merged by tkv_reduce_kernel.
+// partials (m, l, acc) of the items are merged by tkv_reduce_rows_kernel.
 //
 // Matrix cores do both contractions (v_mfma_f32_16x16x32_f16), fp32 accumulate,
 // and the packed codes are never expanded by arithmetic: a masked 16-bit field
 // with a code in its low ten bits *is* the fp16 subnormal code * 2^(pos-24), so
 // unpacking is one AND per two codes, for K and for V.
 //
-//   QK^T  D[token, head] = sum_c code[token, c] * q[head, c]   one MFMA per
-//         (16-token tile, group of 32 channels).  q is converted to fp16 once,
-//         scaled by a power of two (exact) and by 2^-pos per slot; the K scale
-//         (fp32, times the compensating power of two) multiplies the MFMA
-//         result.  The zero-point term sum_g zero[token,g] * sum_{c in g} q[head,c]
-//         is one more MFMA whose A operand is the stored fp16 zero plane.
-//         Head columns 8..15 repeat heads 0..7.
+//   QK^T  D[token, head] = sum_c code[token, c] * q[head, c].  q is converted to fp16
+//         once, scaled by a power of two (exact) and by 2^-pos per slot; the K scale
+//         (fp32, times the compensating power of two) multiplies the MFMA result.  The
+//         eight heads fill half of the 16 columns, so the columns carry two token sets:
+//         row r of a 32-token block is token r in columns 0..7 and token 16 + r in
+//         columns 8..15; an MFMA contracts half a group (16 channels) of both, the B
+//         operand holding q in the k-slots of the column's own set and zeros in the
+//         others.  Scale, exponential and weight pieces are then formed once per
+//         (token, head).  The zero-point term sum_g zero[token,g] * sum_{c in g} q[head,c]
+//         is one more MFMA per block whose A operand is the stored fp16 zero plane.
+//         (Per-channel INT2 keys use the columns differently, see compute_page.)
 //   PV    D[(head, half), channel] = sum_token a[head, token, g] * code[token, channel],
-//         a = fp16(W * scale[token, g]), W the softmax weight in fp16: the V scale
-//         multiplies the weights, not the codes.  Rows 0..7 carry the weights of the
-//         heads for groups 0 and 1, rows 8..15 for groups 2 and 3; the 16 columns of
-//         an MFMA are 8 channels of groups {0,1} and 8 channels of groups {2,3}
-//         (each lane loads its V words accordingly), so every (head, token, group)
-//         product is formed once per wavefront; the two cross quadrants of the
-//         result are never read.
-//         Dequantised value: x = s*c + z = s*(c - c0) + (z + s*c0) for ANY c0.  With
-//         c0 = round(-z/s) the remainder z' = z + s*c0 is at most s/2, and the two
-//         large terms s*c and s*c0 are weighted by the SAME rounded a, so their
-//         cancellation is exact: sum_t a*c0 is one more MFMA (c0 in the slot
-//         encoding of the codes), sum_t W*z' another (z' in two fp16 pieces) whose
-//         ninth column of ones gives the softmax denominator.  The rounding of a
-//         perturbs a token's weight for one group by 2^-12 relative, which moves the
-//         output by at most that fraction of the token's dequantised values.
+//         a = W * scale[token, g], W the softmax weight: the V scale multiplies the
+//         weights, not the codes.  Rows 0..7 carry the weights of the heads for groups 0
+//         and 1, rows 8..15 for groups 2 and 3; the 16 columns of an MFMA are 8 channels
+//         of groups {0,1} and 8 channels of groups {2,3} (each lane loads its V words
+//         accordingly), so every (head, token, group) product is formed once per
+//         wavefront; the two cross quadrants of the result are never read.
+//         The weights must be good to about 2^-17: a group with outlier channels has
+//         |code * scale| and |zero| of tens that cancel, and the tolerance near zero is
+//         2e-3.  W is therefore carried in two fp16 pieces (the leading 11 bits, then the
+//         next 11), and a in two pieces as well: a_hi = fp16(W_hi * s), a_lo = W_lo * s +
+//         the exact remainder of the hi product (packed fp16 FMAs); each V operand meets
+//         both pieces (two MFMAs into the same accumulator).  The zero-point term
+//         sum_t W * zero[t, g] and the softmax denominator sum_t W come from one more
+//         pair of MFMAs per 32 tokens against the stored zero plane and a column of ones.
 //
-// Every product the MFMAs see is exact; the roundings are fp32 accumulation,
-// the fp32 K-scale multiply, the 11-bit softmax weight (common to numerator and
-// denominator) and the 11-bit a.
+// Every product the MFMAs see is exact; the roundings are fp32 accumulation, the fp32
+// K-scale multiply, the 22-bit softmax weight (common to numerator and denominator) and
+// the two-piece a.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -905,87 +908,40 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     }
 }
 
-// D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence.
-// One workgroup of 512 threads per (sequence, query head, slice of CH channels): the items' maxima are reduced in
-// parallel, the weights go to LDS, then 512 / CH groups of CH threads (one thread per channel) each sum every
-// (512 / CH)-th item.  CH = 128 (four groups) when a sequence has tens of items; CH = 16 (32 groups, eight
-// workgroups per head) when it has hundreds, as a single long sequence with one kv head does.
-constexpr int kReduceThreads = 512;
-template <int CH>
-__global__ __launch_bounds__(kReduceThreads) void tkv_reduce_kernel(
+// D7: out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i over the items of a sequence (Sec. 3.2.3: the
+// splits are merged by online log-sum-exp).
+// One workgroup of TH threads per (sequence, query head, one of SL channel slices).  32 / SL lanes own an item at a
+// time: their 16-byte loads are the item's accumulators of the slice, so every partial is read once with 128-bit
+// loads and TH * SL / 32 items are in flight per workgroup round.  Each such lane group keeps a running (M, l, acc);
+// the groups are merged through LDS by the first wavefront.  SL = 1, TH = 256 when a sequence has tens of items;
+// SL = 4, TH = 512 (four workgroups per head, 64 item slots each) when it has hundreds, as a single long sequence
+// with one kv head does.
+template <int SL, int TH>
+__global__ __launch_bounds__(TH) void tkv_reduce_rows_kernel(
     const float *__restrict__ acc_ws, const float *__restrict__ ml_ws, const int32_t *__restrict__ seq_item_indptr,
     int n_q_heads, float *__restrict__ out)
 {
-    constexpr int kThreads = kReduceThreads, kChunk = 512, kParts = kThreads / CH, kSlices = kHeadDim / CH;
-    __shared__ float w_s[kChunk];
-    __shared__ float red[kThreads / 64];
-    __shared__ float part_s[kParts][CH];
-    __shared__ float den_s[kParts];
-    const int bh = blockIdx.x / kSlices, slice = blockIdx.x % kSlices;
+    constexpr int kLanes = 32 / SL;       // lanes per item: 16 bytes each
+    constexpr int kSlots = TH / kLanes;   // items in flight
+    constexpr int kSubsets = 64 / kLanes; // the first wavefront merges the slots in this many interleaved subsets
+    __shared__ float4 num_s[kSlots][kLanes];
+    __shared__ float2 ml_s[kSlots];
+    const int bh = blockIdx.x / SL, slice = blockIdx.x % SL;
     const int b = bh / n_q_heads, h = bh % n_q_heads, tid = threadIdx.x;
-    const int cl = tid % CH, c = slice * CH + cl, part = tid / CH;
-    const int i0 = seq_item_indptr[b], i1 = seq_item_indptr[b + 1];
-    // global maximum of the items' reference maxima
-    float M = -INFINITY;
-    for (int i = i0 + tid; i < i1; i += kThreads) M = fmaxf(M, ml_ws[2 * ((size_t)i * n_q_heads + h)]);
-    M = wave_max(M);
-    if ((tid & 63) == 0) red[tid >> 6] = M;
-    __syncthreads();
-    M = red[0];
-#pragma unroll
-    for (int k = 1; k < kThreads / 64; ++k) M = fmaxf(M, red[k]);
-    float num = 0.0f, den = 0.0f;
-    if (M != -INFINITY) {
-        for (int base = i0; base < i1; base += kChunk) {
-            const int n = i1 - base < kChunk ? i1 - base : kChunk;
-            __syncthreads();
-            if (tid < n) w_s[tid] = __builtin_amdgcn_exp2f(ml_ws[2 * ((size_t)(base + tid) * n_q_heads + h)] - M);
-            __syncthreads();
-#pragma unroll 4
-            for (int k = part; k < n; k += kParts) {
-                const size_t ph = (size_t)(base + k) * n_q_heads + h;
-                num = fmaf(w_s[k], acc_ws[ph * kHeadDim + c], num);
-                if (cl == 0) den = fmaf(w_s[k], ml_ws[2 * ph + 1], den);
-            }
-        }
-    }
-    part_s[part][cl] = num;
-    if (cl == 0) den_s[part] = den;
-    __syncthreads();
-    if (part == 0) {
-        float nsum = 0.0f, dsum = 0.0f;
-#pragma unroll
-        for (int k = 0; k < kParts; ++k) { nsum += part_s[k][cl]; dsum += den_s[k]; }
-        out[((size_t)b * n_q_heads + h) * kHeadDim + c] = dsum > 0.0f ? nsum / dsum : 0.0f;
-    }
-}
-
-
-// D7 for sequences with tens of items at most: one workgroup of four wavefronts per (sequence, query head).  A
-// half wavefront owns an item at a time: 32 lanes x 16 bytes are the item's 128 accumulators, so every partial is
-// read once with 128-bit loads and eight items are in flight per workgroup round.  Each half wavefront keeps a
-// running (M, l, acc) and the eight of them are merged through LDS.
-constexpr int kRowsThreads = 256;
-__global__ __launch_bounds__(kRowsThreads) void tkv_reduce_rows_kernel(
-    const float *__restrict__ acc_ws, const float *__restrict__ ml_ws, const int32_t *__restrict__ seq_item_indptr,
-    int n_q_heads, float *__restrict__ out)
-{
-    constexpr int kHalves = kRowsThreads / 32;   // 8
-    __shared__ float4 num_s[kHalves][32];
-    __shared__ float2 ml_s[kHalves];
-    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, tid = threadIdx.x;
-    const int half = tid >> 5, cq = tid & 31;
+    const int slot = tid / kLanes, ln = tid % kLanes, cq = slice * kLanes + ln;   // cq: which float4 of the 32 of a row
     const int i0 = seq_item_indptr[b], i1 = seq_item_indptr[b + 1];
     float M = -INFINITY, den = 0.0f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
-    for (int i = i0 + half; i < i1; i += kHalves) {
+    for (int i = i0 + slot; i < i1; i += kSlots) {
         const size_t ph = (size_t)i * n_q_heads + h;
         const float2 ml = reinterpret_cast<const float2 *>(ml_ws)[ph];
         const float4 a = reinterpret_cast<const float4 *>(acc_ws + ph * kHeadDim)[cq];
-        if (ml.x == -INFINITY) continue;   // an item without tokens
+        // an item without tokens has m = -inf, l = 0 and weighs nothing; no branch, so the loads of several
+        // rounds are in flight together
         const float Mn = fmaxf(M, ml.x);
-        const float so = __builtin_amdgcn_exp2f(M - Mn), sn = __builtin_amdgcn_exp2f(ml.x - Mn);   // exp2(-inf) = 0 the first time
+        const float so = M == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(M - Mn);
+        const float sn = ml.x == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(ml.x - Mn);
         den = den * so + sn * ml.y;
         num.x = num.x * so + sn * a.x;
         num.y = num.y * so + sn * a.y;
@@ -993,30 +949,40 @@ __global__ __launch_bounds__(kRowsThreads) void tkv_reduce_rows_kernel(
         num.w = num.w * so + sn * a.w;
         M = Mn;
     }
-    num_s[half][cq] = num;
-    if (cq == 0) ml_s[half] = make_float2(M, den);
+    num_s[slot][ln] = num;
+    if (ln == 0) ml_s[slot] = make_float2(M, den);
     __syncthreads();
-    if (tid < 32) {
+    if (tid < 64) {
+        // lane (subset, ln) of the first wavefront merges slots subset, subset + kSubsets, ...
         float Mg = -INFINITY;
 #pragma unroll
-        for (int k = 0; k < kHalves; ++k) Mg = fmaxf(Mg, ml_s[k].x);
+        for (int k = slot; k < kSlots; k += kSubsets) Mg = fmaxf(Mg, ml_s[k].x);
+#pragma unroll
+        for (int o = kLanes; o < 64; o <<= 1) Mg = fmaxf(Mg, __shfl_xor(Mg, o));
         float4 n = make_float4(0.f, 0.f, 0.f, 0.f);
         float d = 0.0f;
-        if (Mg != -INFINITY) {
 #pragma unroll
-            for (int k = 0; k < kHalves; ++k) {
-                const float2 ml = ml_s[k];
-                const float wk = ml.x == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(ml.x - Mg);
-                const float4 a = num_s[k][tid];
-                d += wk * ml.y;
-                n.x += wk * a.x;
-                n.y += wk * a.y;
-                n.z += wk * a.z;
-                n.w += wk * a.w;
-            }
+        for (int k = slot; k < kSlots; k += kSubsets) {
+            const float2 ml = ml_s[k];
+            const float wk = ml.x == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(ml.x - Mg);
+            const float4 a = num_s[k][ln];
+            d += wk * ml.y;
+            n.x += wk * a.x;
+            n.y += wk * a.y;
+            n.z += wk * a.z;
+            n.w += wk * a.w;
+        }
+#pragma unroll
+        for (int o = kLanes; o < 64; o <<= 1) {
+            d += __shfl_xor(d, o);
+            n.x += __shfl_xor(n.x, o);
+            n.y += __shfl_xor(n.y, o);
+            n.z += __shfl_xor(n.z, o);
+            n.w += __shfl_xor(n.w, o);
         }
         const float r = d > 0.0f ? 1.0f / d : 0.0f;
-        reinterpret_cast<float4 *>(out + ((size_t)b * n_q_heads + h) * kHeadDim)[tid] = make_float4(n.x * r, n.y * r, n.z * r, n.w * r);
+        if (tid < kLanes)
+            reinterpret_cast<float4 *>(out + ((size_t)b * n_q_heads + h) * kHeadDim)[cq] = make_float4(n.x * r, n.y * r, n.z * r, n.w * r);
     }
 }
 
@@ -1047,14 +1013,11 @@ int tkv_launch_decode_reduce(const tkv_desc *desc, const int32_t *seq_item_indpt
     const float *acc_ws = (const float *)workspace;
     const float *ml_ws = acc_ws + (size_t)n_items * n_q_heads * kHeadDim;
     // the item counts are on the device; the average per sequence picks the shape of the reduction
-    if ((int64_t)n_items <= 64 * (int64_t)batch)
-        hipLaunchKernelGGL(tkv_reduce_rows_kernel, dim3((unsigned)(batch * n_q_heads)), dim3(kRowsThreads), 0,
-                           (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
-    else if ((int64_t)n_items > 128 * (int64_t)batch)
-        hipLaunchKernelGGL(tkv_reduce_kernel<16>, dim3((unsigned)(batch * n_q_heads * (kHeadDim / 16))), dim3(kReduceThreads), 0,
+    if ((int64_t)n_items <= 128 * (int64_t)batch)
+        hipLaunchKernelGGL((tkv_reduce_rows_kernel<1, 256>), dim3((unsigned)(batch * n_q_heads)), dim3(256), 0,
                            (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     else
-        hipLaunchKernelGGL(tkv_reduce_kernel<128>, dim3((unsigned)(batch * n_q_heads)), dim3(kReduceThreads), 0,
+        hipLaunchKernelGGL((tkv_reduce_rows_kernel<4, 512>), dim3((unsigned)(batch * n_q_heads * 4)), dim3(512), 0,
                            (hipStream_t)stream, acc_ws, ml_ws, seq_item_indptr, n_q_heads, out);
     return hipGetLastError() == hipSuccess ? TKV_OK : TKV_ERR_HIP;
 }
