@@ -129,11 +129,36 @@ __device__ __forceinline__ uint32_t ror8_u32(uint32_t v)
 {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
 }
+// The value of another lane of the same row of 16 lanes: CTRL is a DPP pattern under which every lane has a source.
+template <int CTRL> __device__ __forceinline__ float row_dpp(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+// Sum / maximum over a row of 16 lanes, in every lane of the row: neighbours, pairs, quads, halves
+// (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror).
+__device__ __forceinline__ float row_sum(float v)
+{
+    v += row_dpp<0xB1>(v);
+    v += row_dpp<0x4E>(v);
+    v += row_dpp<0x141>(v);
+    v += row_dpp<0x140>(v);
+    return v;
+}
+__device__ __forceinline__ float row_max(float v)
+{
+    v = fmaxf(v, row_dpp<0xB1>(v));
+    v = fmaxf(v, row_dpp<0x4E>(v));
+    v = fmaxf(v, row_dpp<0x141>(v));
+    v = fmaxf(v, row_dpp<0x140>(v));
+    return v;
+}
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = row_max(v);
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 // Orders this wavefront's LDS writes before its later LDS reads.  The workgroup is one wavefront
 // and LDS operations of a wavefront execute in order, so no wait and no barrier instruction is needed.
@@ -159,7 +184,12 @@ constexpr int kQyStride = 17, kQyZero = 16;
 constexpr int kPvZ = 0, kPvS = 32, kPvZero = 64, kPvOne = 65, kPvChunks = 66;
 
 // Only the kernel for per-channel INT2 keys holds the second q operand.
-template <bool KC> struct LdsExtra {};
+template <bool KC> struct LdsExtra {
+    // q * 2^E per head and channel, kept for the whole item.  Rows are 16 bytes longer than the 256 they hold: the
+    // operand build reads the same channels of all eight heads at once, and 256-byte rows would put them on the
+    // same LDS banks
+    alignas(16) _Float16 qf[8][kHeadDim + 8];
+};
 template <> struct LdsExtra<true> {
     alignas(16) uint4 qp[kGroups][64];                   // q * 2^E in the slot order of qo, without the slot factors
 };
@@ -217,28 +247,28 @@ __device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head
     } else {
         uint4 *qy = reinterpret_cast<uint4 *>(lds.qo);
         const int sub = q4 & 1, ent = sub * 8 + (lane & 7);   // lanes that differ in lane & 8 or q4 & 2 write the same entry
+        // the slot factors are powers of two and q * 2^E has 8 significant bits: the fp16 products are exact
+        // unless they fall into the subnormals, where they round once
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
             for (int hg = 0; hg < 2; ++hg) {
                 uint32_t r[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    int c0, c1;
-                    float f;
-                    if (BITS == 4) {
-                        // registers: (n0,n4) (n1,n5)*16 (n2,n6) (n3,n7)*16 of the 8-channel word 2*hg + sub of the group
-                        const int nib = (k & 1) + 2 * (k >> 1);
-                        c0 = 32 * g + 8 * (2 * hg + sub) + nib;
-                        c1 = c0 + 4;
-                        f = (k & 1) ? 0.0625f : 1.0f;
-                    } else {
-                        // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^(2k+3) of the 16-channel word hg of the group
-                        c0 = 32 * g + 16 * hg + 4 * sub + k;
-                        c1 = c0 + 8;
-                        f = 1.0f / (float)(1 << (2 * k + 3));
-                    }
-                    r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
+                if (BITS == 4) {
+                    // registers: (n0,n4) (n1,n5)/16 (n2,n6) (n3,n7)/16 of the 8-channel word 2*hg + sub of the group
+                    const uint4 c = reinterpret_cast<const uint4 *>(qf)[g * 4 + 2 * hg + sub];   // channels (0,1) (2,3) (4,5) (6,7)
+                    r[0] = __builtin_amdgcn_perm(c.z, c.x, 0x05040100u);
+                    r[1] = pk_mul(__builtin_amdgcn_perm(c.z, c.x, 0x07060302u), 0x2c002c00u);
+                    r[2] = __builtin_amdgcn_perm(c.w, c.y, 0x05040100u);
+                    r[3] = pk_mul(__builtin_amdgcn_perm(c.w, c.y, 0x07060302u), 0x2c002c00u);
+                } else {
+                    // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^-(2k+3) of the 16-channel word hg of the group
+                    const uint2 x = reinterpret_cast<const uint2 *>(qf)[g * 8 + 4 * hg + sub];       // channels 4*sub + 0..3
+                    const uint2 y = reinterpret_cast<const uint2 *>(qf)[g * 8 + 4 * hg + sub + 2];   // channels 8 + 4*sub + 0..3
+                    r[0] = pk_mul(__builtin_amdgcn_perm(y.x, x.x, 0x05040100u), 0x30003000u);
+                    r[1] = pk_mul(__builtin_amdgcn_perm(y.x, x.x, 0x07060302u), 0x28002800u);
+                    r[2] = pk_mul(__builtin_amdgcn_perm(y.y, x.y, 0x05040100u), 0x20002000u);
+                    r[3] = pk_mul(__builtin_amdgcn_perm(y.y, x.y, 0x07060302u), 0x18001800u);
                 }
                 qy[(g * 2 + hg) * kQyStride + ent] = make_uint4(r[0], r[1], r[2], r[3]);
             }
@@ -725,10 +755,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
 {
     using QF = _Float16;   // q * 2^E is exact in fp16 (q has 8 significant bits)
     __shared__ Lds<KC> lds;
-    // q * 2^E per head and channel (2 KiB of fp16), read while the MFMA operands are built: it lives in the page
-    // staging area ks | pv, which is idle then, so that twelve wavefronts fit the LDS of a compute unit; it is
-    // written again before the INT4 operand is built.
-    QF(*qf)[kHeadDim] = reinterpret_cast<QF(*)[kHeadDim]>(lds.ks);
+    // q * 2^E per head and channel (2 KiB of fp16), read while the MFMA operands are built.  With per-channel INT2
+    // keys it lives in the page staging area ks | pv, which is idle then, so that twelve wavefronts fit the LDS of a
+    // compute unit, and is written again before the INT4 operand is built; otherwise it has its own place.
+    constexpr int kQfRow = KC ? kHeadDim : kHeadDim + 8;
+    QF(*qf)[kQfRow];
+    if constexpr (KC) qf = reinterpret_cast<QF(*)[kQfRow]>(lds.ks);
+    else qf = lds.qf;
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
@@ -806,9 +839,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
         reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(qv[h][0] * two_e, qv[h][1] * two_e);
-        float sum = qv[h][0] + qv[h][1];
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o);
+        const float sum = row_sum(qv[h][0] + qv[h][1]);
         if (r16 == 0) lds.zl()[h][q4] = sum;   // [head][group]
     }
     lds_order();
@@ -854,7 +885,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     }
     if (has4) {
         start_pages<4, KC>(cx, wr4, s4);
-        if (has2) {   // the INT2 pages have used that memory since
+        if (KC && has2) {   // the INT2 pages have used that memory since
             lds_order();
 #pragma unroll
             for (int h = 0; h < 8; ++h) {
