@@ -912,13 +912,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     lds_order();
     const float unscale = ldexpf(1.0f, 24 - kVExp);
     const int hb = r16 >> 3;
+    // The accumulators go through an LDS tile [head][channel] so that every lane stores 16 bytes and a store
+    // instruction covers two whole heads (a lane holds single channels of four heads).  The tile takes the start of
+    // the LDS, which holds nothing the epilogue needs (q staging, page staging); rows are 16 bytes longer than a
+    // head so that heads h and h + 4, written by the same instruction, fall on different banks.
+    constexpr int kOutRow = kHeadDim + 4;
+    static_assert(sizeof(LdsExtra<KC>) + sizeof(float) * kPageTokens * kGroups + sizeof(uint4) * kPvChunks >= 8 * kOutRow * sizeof(float),
+                  "the output tile must fit in what precedes kz, qo (= zl()) and alpha in Lds");
+    float *tile = reinterpret_cast<float *>(&lds);
     if ((q4 >> 1) == hb) {   // the quadrants whose rows and columns belong to the same pair of groups
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int head = 4 * (q4 & 1) + i;
-            if (head >= R) continue;
-            const size_t ph = (size_t)item * n_q_heads + kvh * R + head;
-            float *dst = acc_ws + ph * kHeadDim + 64 * hb;
 #pragma unroll
             for (int gg = 0; gg < 2; ++gg) {
                 const int g = 2 * hb + gg;
@@ -928,13 +933,22 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
 #pragma unroll
                     for (int cc = 0; cc < 2; ++cc) {
                         const int comp = 2 * gg + cc;
-                        dst[16 * comp + (chunk ? r16 ^ 8 : r16)] = st.acc[chunk][comp][i] * unscale + zsum;
+                        tile[head * kOutRow + 64 * hb + 16 * comp + (chunk ? r16 ^ 8 : r16)] = st.acc[chunk][comp][i] * unscale + zsum;
                     }
             }
-            if ((r16 & 7) == 0 && hb == 0) {
-                ml_ws[2 * ph] = lds.alpha[head];
-                ml_ws[2 * ph + 1] = lds.zl()[head][4];
-            }
+        }
+    }
+    if (lane < 8 && lane < R) {
+        const size_t ph = (size_t)item * n_q_heads + kvh * R + lane;
+        reinterpret_cast<float2 *>(ml_ws)[ph] = make_float2(lds.alpha[lane], lds.zl()[lane][4]);
+    }
+    lds_order();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int head = 2 * k + (lane >> 5), c4 = lane & 31;
+        if (head < R) {
+            const size_t ph = (size_t)item * n_q_heads + kvh * R + head;
+            reinterpret_cast<float4 *>(acc_ws + ph * kHeadDim)[c4] = reinterpret_cast<const float4 *>(tile + head * kOutRow)[c4];
         }
     }
 }
