@@ -185,10 +185,7 @@ constexpr int kPvZ = 0, kPvS = 32, kPvZero = 64, kPvOne = 65, kPvChunks = 66;
 
 // Only the kernel for per-channel INT2 keys holds the second q operand.
 template <bool KC> struct LdsExtra {
-    // q * 2^E per head and channel, kept for the whole item.  Rows are 16 bytes longer than the 256 they hold: the
-    // operand build reads the same channels of all eight heads at once, and 256-byte rows would put them on the
-    // same LDS banks
-    alignas(16) _Float16 qf[8][kHeadDim + 8];
+    alignas(16) _Float16 qf[8][kHeadDim + 8];            // q * 2^E per head and channel (qf_chunk), kept for the whole item
 };
 template <> struct LdsExtra<true> {
     alignas(16) uint4 qp[kGroups][64];                   // q * 2^E in the slot order of qo, without the slot factors
@@ -218,37 +215,55 @@ template <bool KC> struct alignas(16) Lds : LdsExtra<KC> {
     __device__ __forceinline__ uint4 *kc_nil() { return reinterpret_cast<uint4 *>(kz); }
 };
 
+// q * 2^E is staged in LDS as fp16 [head][128 channels].  The operand build reads the same channels of all eight
+// heads at once; with plain 256-byte rows those reads would all fall on the same banks.  The kernel for per-token
+// keys, which has the room, makes the rows 272 bytes long; the kernel for per-channel INT2 keys keeps 256-byte rows
+// (the staging area it borrows holds no more) and stores the 16-byte chunks of a row at chunk ^ head instead.
+// Byte offset of 16-byte chunk `chunk` (8 channels) of head `h`:
+template <bool KC> __device__ __forceinline__ int qf_chunk(int h, int chunk)
+{
+    return KC ? h * 256 + ((chunk ^ h) << 4) : h * 272 + (chunk << 4);
+}
+// lane l of a wavefront holds channels 2l, 2l+1 of a head as an fp16 pair
+template <bool KC> __device__ __forceinline__ void qf_store(void *qf, int h, int lane, uint32_t pair)
+{
+    *reinterpret_cast<uint32_t *>(static_cast<char *>(qf) + qf_chunk<KC>(h, lane >> 2) + ((lane & 3) << 2)) = pair;
+}
+
 // B operand of the QK^T MFMAs for one width, kept in LDS: 4 registers of fp16 pairs holding
 // q' = q * 2^E * 2^-pos in the slot order the unpack produces.
 //  - per-channel INT2 keys: per group and lane (head columns 8..15 repeat heads 0..7), plus the copy without
 //    slot factors;
 //  - otherwise (two token sets, see compute_page): per (group, half group) one entry per (channel octet sub,
 //    head) and an entry of zeros, which the lanes whose k-slots belong to the other token set read.
-template <int BITS, bool KC, class QF>
-__device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head, 128 values q * 2^E in LDS */, int q4,
-                                               int lane, Lds<KC> &lds)
+// The slot factors are powers of two and q * 2^E has 8 significant bits: the fp16 products are exact unless they
+// fall into the subnormals, where they round once.
+template <int BITS, bool KC>
+__device__ __forceinline__ void build_q_operand(const void *qf /* the staged q (qf_chunk) */, int h /* this lane's head */,
+                                               int q4, int lane, Lds<KC> &lds)
 {
+    const char *qb = static_cast<const char *>(qf);
+    // INT2 words: registers (crumb 4*sub+k, crumb 8+4*sub+k) * 2^-(2k+3), k = 0..3, of 16-channel word hg of a group
+    auto int2_pairs = [&](int g, int hg, int sub, uint32_t (&pr)[4]) {
+        const uint2 x = *reinterpret_cast<const uint2 *>(qb + qf_chunk<KC>(h, g * 4 + 2 * hg) + 8 * sub);       // channels 4*sub + 0..3
+        const uint2 y = *reinterpret_cast<const uint2 *>(qb + qf_chunk<KC>(h, g * 4 + 2 * hg + 1) + 8 * sub);   // channels 8 + 4*sub + 0..3
+        pr[0] = __builtin_amdgcn_perm(y.x, x.x, 0x05040100u);
+        pr[1] = __builtin_amdgcn_perm(y.x, x.x, 0x07060302u);
+        pr[2] = __builtin_amdgcn_perm(y.y, x.y, 0x05040100u);
+        pr[3] = __builtin_amdgcn_perm(y.y, x.y, 0x07060302u);
+    };
+    constexpr uint32_t kSlot2[4] = {0x30003000u, 0x28002800u, 0x20002000u, 0x18001800u};   // fp16 2^-3, 2^-5, 2^-7, 2^-9 twice
     if constexpr (KC && BITS == 2) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            uint32_t r[4], rp[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^(2k+3) of the 16-channel word q4/2
-                const int c0 = 32 * g + 16 * (q4 >> 1) + 4 * (q4 & 1) + k, c1 = c0 + 8;
-                // the unpack leaves the field of slot k at bit 2k + 3 (see compute_page)
-                const float f = 1.0f / (float)(1 << (2 * k + 3));
-                r[k] = pack_h2((float)qf[c0] * f, (float)qf[c1] * f);
-                rp[k] = pack_h2((float)qf[c0], (float)qf[c1]);
-            }
-            lds.qo[g][lane] = make_uint4(r[0], r[1], r[2], r[3]);
+            uint32_t rp[4];
+            int2_pairs(g, q4 >> 1, q4 & 1, rp);   // the unpack leaves the field of slot k at bit 2k + 3 (see compute_page)
+            lds.qo[g][lane] = make_uint4(pk_mul(rp[0], kSlot2[0]), pk_mul(rp[1], kSlot2[1]), pk_mul(rp[2], kSlot2[2]), pk_mul(rp[3], kSlot2[3]));
             lds.qp[g][lane] = make_uint4(rp[0], rp[1], rp[2], rp[3]);
         }
     } else {
         uint4 *qy = reinterpret_cast<uint4 *>(lds.qo);
         const int sub = q4 & 1, ent = sub * 8 + (lane & 7);   // lanes that differ in lane & 8 or q4 & 2 write the same entry
-        // the slot factors are powers of two and q * 2^E has 8 significant bits: the fp16 products are exact
-        // unless they fall into the subnormals, where they round once
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -256,19 +271,15 @@ __device__ __forceinline__ void build_q_operand(const QF *qf /* this lane's head
                 uint32_t r[4];
                 if (BITS == 4) {
                     // registers: (n0,n4) (n1,n5)/16 (n2,n6) (n3,n7)/16 of the 8-channel word 2*hg + sub of the group
-                    const uint4 c = reinterpret_cast<const uint4 *>(qf)[g * 4 + 2 * hg + sub];   // channels (0,1) (2,3) (4,5) (6,7)
+                    const uint4 c = *reinterpret_cast<const uint4 *>(qb + qf_chunk<KC>(h, g * 4 + 2 * hg + sub));   // channels (0,1) (2,3) (4,5) (6,7)
                     r[0] = __builtin_amdgcn_perm(c.z, c.x, 0x05040100u);
                     r[1] = pk_mul(__builtin_amdgcn_perm(c.z, c.x, 0x07060302u), 0x2c002c00u);
                     r[2] = __builtin_amdgcn_perm(c.w, c.y, 0x05040100u);
                     r[3] = pk_mul(__builtin_amdgcn_perm(c.w, c.y, 0x07060302u), 0x2c002c00u);
                 } else {
-                    // registers: (crumb 4*sub+k, crumb 8+4*sub+k) * 2^-(2k+3) of the 16-channel word hg of the group
-                    const uint2 x = reinterpret_cast<const uint2 *>(qf)[g * 8 + 4 * hg + sub];       // channels 4*sub + 0..3
-                    const uint2 y = reinterpret_cast<const uint2 *>(qf)[g * 8 + 4 * hg + sub + 2];   // channels 8 + 4*sub + 0..3
-                    r[0] = pk_mul(__builtin_amdgcn_perm(y.x, x.x, 0x05040100u), 0x30003000u);
-                    r[1] = pk_mul(__builtin_amdgcn_perm(y.x, x.x, 0x07060302u), 0x28002800u);
-                    r[2] = pk_mul(__builtin_amdgcn_perm(y.y, x.y, 0x05040100u), 0x20002000u);
-                    r[3] = pk_mul(__builtin_amdgcn_perm(y.y, x.y, 0x07060302u), 0x18001800u);
+                    int2_pairs(g, hg, sub, r);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) r[k] = pk_mul(r[k], kSlot2[k]);
                 }
                 qy[(g * 2 + hg) * kQyStride + ent] = make_uint4(r[0], r[1], r[2], r[3]);
             }
@@ -377,11 +388,15 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             vsc.x &= m01; vsc.y &= m23; vzc.x &= m01; vzc.y &= m23;
         }
         if constexpr (kPerChannel) {
-            // the two key metadata planes as stored: fp16 [block][128 channel positions]
-            const uint32_t k01 = pk_min(pr.ksc.x, kKcClamp), k23 = pk_min(pr.ksc.y, kKcClamp);
-            st.sat |= (k01 ^ pr.ksc.x) | (k23 ^ pr.ksc.y);
+            // the two key metadata planes as stored: fp16 [block][128 channel positions]; lanes 0..31 hold block 0.
+            // A block that was never written (a half-filled page) is masked by count like everything else: whatever
+            // its planes hold is neither used nor reported as a saturated scale.
+            const bool dead = partial && 32 * (lane >> 5) >= n_valid;
+            const uint2 ks = dead ? make_uint2(0u, 0u) : pr.ksc, kz = dead ? make_uint2(0u, 0u) : pr.kzc;
+            const uint32_t k01 = pk_min(ks.x, kKcClamp), k23 = pk_min(ks.y, kKcClamp);
+            st.sat |= (k01 ^ ks.x) | (k23 ^ ks.y);
             reinterpret_cast<uint2 *>(lds.kc_scale())[lane] = make_uint2(k01, k23);
-            reinterpret_cast<uint2 *>(lds.kc_zero())[lane] = pr.kzc;
+            reinterpret_cast<uint2 *>(lds.kc_zero())[lane] = kz;
         } else {
             const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
             reinterpret_cast<float4 *>(lds.ks)[lane] =
@@ -753,14 +768,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     float kappa, float *__restrict__ acc_ws, float *__restrict__ ml_ws, int32_t *status
     )
 {
-    using QF = _Float16;   // q * 2^E is exact in fp16 (q has 8 significant bits)
     __shared__ Lds<KC> lds;
     // q * 2^E per head and channel (2 KiB of fp16), read while the MFMA operands are built.  With per-channel INT2
     // keys it lives in the page staging area ks | pv, which is idle then, so that twelve wavefronts fit the LDS of a
     // compute unit, and is written again before the INT4 operand is built; otherwise it has its own place.
-    constexpr int kQfRow = KC ? kHeadDim : kHeadDim + 8;
-    QF(*qf)[kQfRow];
-    if constexpr (KC) qf = reinterpret_cast<QF(*)[kQfRow]>(lds.ks);
+    void *qf;
+    if constexpr (KC) qf = lds.ks;
     else qf = lds.qf;
     const int lane = threadIdx.x, r16 = lane & 15, q4 = lane >> 4;
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
@@ -838,7 +851,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     // q * 2^E to LDS; per-group sums of the unscaled q: lanes 16g .. 16g+15 hold group g
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
-        reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(qv[h][0] * two_e, qv[h][1] * two_e);
+        qf_store<KC>(qf, h, lane, pack_h2(qv[h][0] * two_e, qv[h][1] * two_e));   // exact: q has 8 significant bits
         const float sum = row_sum(qv[h][0] + qv[h][1]);
         if (r16 == 0) lds.zl()[h][q4] = sum;   // [head][group]
     }
@@ -873,7 +886,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     st.sat = 0;
 
     if (has2) {
-        build_q_operand<2, KC>(qf[hcol], q4, lane, lds);
+        build_q_operand<2, KC>(qf, hcol, q4, lane, lds);
         LaneConst lc2 = lc;
         if constexpr (KC) {
             lc2.kappa = lc.kappa * lc.F;   // the power of two that the K scale carries otherwise
@@ -892,11 +905,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
                 uint32_t two = 0;
                 if (h < R) two = reinterpret_cast<const uint32_t *>(q + ((size_t)seq * n_q_heads + kvh * R + h) * kHeadDim)[lane];
                 const float q0 = __uint_as_float(two << 16) * two_e, q1 = __uint_as_float(two & 0xffff0000u) * two_e;
-                reinterpret_cast<uint32_t *>(qf[h])[lane] = pack_h2(q0, q1);
+                qf_store<KC>(qf, h, lane, pack_h2(q0, q1));
             }
             lds_order();
         }
-        build_q_operand<4, KC>(qf[hcol], q4, lane, lds);
+        build_q_operand<4, KC>(qf, hcol, q4, lane, lds);
         lds_order();
         run_pages<4, KC>(cx, wr4, s4, pe, pe - pb, qz, lc, st, lds);
     }

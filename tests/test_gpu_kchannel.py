@@ -162,6 +162,22 @@ def test_decode_parity(G, seq_lens, hq, hkv, items):
         cache.close()
 
 
+def test_unwritten_blocks_never_matter(G):
+    """A half-filled INT2 page (one block of 32 tokens): whatever the pool held before in the other block's key
+    planes (zeros, NaN patterns, fp16 numbers beyond the scale limit) neither changes an output bit nor raises
+    the saturation flag (gpu_decode asserts that the status word stays 0)."""
+    q, K, V, seq_bits = G.random_case(23, [96, 32], 8, 1, f4=0.0)
+    outs = []
+    for fill in (0x00, 0xFF, 0x7C, 0x7B):
+        cache, _ = G.kc_check_append(seq_bits, K, V, 1, fill=fill)
+        try:
+            outs.append(G.gpu_decode(cache, q, 3))
+        finally:
+            cache.close()
+    for o in outs[1:]:
+        assert np.array_equal(outs[0], o)
+
+
 def test_decode_all_int2_and_outlier_channels(G):
     """Keys with strong outlier channels, every token INT2: the case the scheme exists for."""
     q, K, V, _ = G.random_case(18, [2048], 8, 1)
