@@ -156,15 +156,16 @@ def test_decode_on_oracle_packed_pool(G):
 
 
 def test_unwritten_slots_never_matter(G):
-    """Same tokens, pool pre-filled with different garbage (0x00, 0xFF = NaN
-    patterns in the metadata planes): identical output bits."""
+    """Same tokens, pool pre-filled with different garbage (0x00, 0xFF and 0x7C = NaN
+    patterns in the metadata planes, 0x7B = fp16 numbers beyond the V scale limit):
+    identical output bits, and no status bit (gpu_decode asserts that)."""
     q, K, V, seq_bits = G.random_case(19, [100, 37], 8, 1)
     outs = []
-    for fill in (0x00, 0xFF, 0x7C):
+    for fill in (0x00, 0xFF, 0x7C, 0x7B):
         cache, _ = G.check_append(seq_bits, K, V, 1, fill=fill)
         outs.append(G.gpu_decode(cache, q, 3))
         cache.close()
-    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
 
 
 def test_bitmap_mismatch_is_flagged(G):
