@@ -309,9 +309,16 @@ int tkv_gather_dequant(const tkv_desc *desc, const void *pool, const uint8_t *bi
  *   n_tok_int2/4  host i32[batch], valid tokens per width (last page may be partial;
  *                 with TKV_KEYS_PER_CHANNEL n_tok_int2 must be a multiple of 32)
  *   target_items  wanted number of items over the whole batch (>= 1)
- *   items_out     host i32[4*capacity]: {sequence, first page, end page, 0},
- *                 page indices relative to the sequence's list
- *   seq_item_indptr_out  host i32[batch+1]: items of sequence b are
+ *   items_out     host i32[4*capacity]: {sequence, first page, end page, partial
+ *                 slot}, page indices relative to the sequence's list.  Items
+ *                 are listed in LAUNCH order (the kernel runs item k as its
+ *                 k-th group of workgroups): by falling share of INT2 pages,
+ *                 so that the wavefronts that end up on one SIMD mix ranges
+ *                 that keep it busy (INT2) with ranges that mostly wait for
+ *                 memory (INT4).  The partial of an item is written to slot
+ *                 `partial slot` of the workspace; the slots are a permutation
+ *                 of 0 .. n_items-1 in sequence order.
+ *   seq_item_indptr_out  host i32[batch+1]: sequence b owns the partial slots
  *                 [indptr[b], indptr[b+1]); a sequence without tokens has none
  * Returns the number of items (>= 0) or a negative status.
  */
@@ -344,9 +351,15 @@ size_t tkv_decode_workspace_bytes(const tkv_desc *desc, int32_t n_items, int32_t
  *   out            device fp32 [batch, n_q_heads, head_dim]
  *   workspace      device, >= tkv_decode_workspace_bytes(...), 16-byte aligned
  *   status         device i32, may be NULL
- *   items          every item must name a sequence of the batch; one that does
- *                  not contributes nothing and raises TKV_STATUS_BAD_ITEM.  The
- *                  page range of an item is clamped to the sequence's pages.
+ *   items          every item must name a sequence of the batch and a partial
+ *                  slot below n_items, each slot once, the slots of a sequence
+ *                  as seq_item_indptr lists them.  An item that names no
+ *                  sequence of the batch contributes nothing (an empty partial
+ *                  in its slot) and raises TKV_STATUS_BAD_ITEM; so does one
+ *                  with a slot out of range, which cannot write anything: the
+ *                  sequence that owns the slot it should have named then reads
+ *                  what the workspace held before.  The page range of an item
+ *                  is clamped to the sequence's pages.
  * The page tables on the device must describe the same sequences as the host
  * arrays the plan was made from (tkv_plan_decode above says when a plan ages).
  * Preconditions on the cache contents: stored scales and zeros finite; V scales

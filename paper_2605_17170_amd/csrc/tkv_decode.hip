@@ -779,10 +779,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     const int item = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
     const int R = n_q_heads / n_kv_heads;
     const int seq = items[4 * item];
-    if (seq < 0 || seq >= batch) {
-        // malformed item: an empty partial (m = -inf, l = 0), which the merge ignores, and a status bit
-        for (int h = 0; h < R; ++h) {
-            const size_t ph = (size_t)item * n_q_heads + kvh * R + h;
+    // The partial of this item goes to slot items[4*item + 3] of the workspace: items are listed in launch order,
+    // the slots of a sequence are contiguous (the merge reads them by sequence).
+    const int slot = items[4 * item + 3];
+    const bool slot_ok = slot >= 0 && slot < (int)(gridDim.x / n_kv_heads);
+    if (seq < 0 || seq >= batch || !slot_ok) {
+        // malformed item: an empty partial (m = -inf, l = 0), which the merge ignores, and a status bit; with a slot
+        // outside the workspace nothing can be written, and whoever owns the slot it should have named reads what
+        // the workspace held before
+        for (int h = 0; h < R && slot_ok; ++h) {
+            const size_t ph = (size_t)slot * n_q_heads + kvh * R + h;
             reinterpret_cast<float2 *>(acc_ws + ph * kHeadDim)[lane] = make_float2(0.0f, 0.0f);
             if (lane == 0) reinterpret_cast<float2 *>(ml_ws)[ph] = make_float2(-INFINITY, 0.0f);
         }
@@ -952,7 +958,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
         }
     }
     if (lane < 8 && lane < R) {
-        const size_t ph = (size_t)item * n_q_heads + kvh * R + lane;
+        const size_t ph = (size_t)slot * n_q_heads + kvh * R + lane;
         reinterpret_cast<float2 *>(ml_ws)[ph] = make_float2(lds.alpha[lane], lds.zl()[lane][4]);
     }
     lds_order();
@@ -960,7 +966,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     for (int k = 0; k < 4; ++k) {
         const int head = 2 * k + (lane >> 5), c4 = lane & 31;
         if (head < R) {
-            const size_t ph = (size_t)item * n_q_heads + kvh * R + head;
+            const size_t ph = (size_t)slot * n_q_heads + kvh * R + head;
             reinterpret_cast<float4 *>(acc_ws + ph * kHeadDim)[c4] = reinterpret_cast<const float4 *>(tile + head * kOutRow)[c4];
         }
     }

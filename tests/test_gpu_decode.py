@@ -221,7 +221,7 @@ def test_item_naming_a_sequence_outside_the_batch_is_flagged_and_contributes_not
         ref = G.decode_ref(q, Kq, Vq, [400, 200])
         items, sip = cache.plan_decode(6)
         bad = items.copy()
-        k = int(sip[1]) - 1                      # the last item of sequence 0 is replaced by a malformed one
+        k = int(np.nonzero(items[:, 3] == sip[1] - 1)[0][0])   # the last item of sequence 0 is replaced by a malformed one
         lost = bad[k].copy()
         bad[k, 0] = 7
         cache._plan = (torch.from_numpy(bad).to(G.DEV), cache._plan[1], bad, sip)
@@ -246,6 +246,31 @@ def test_item_naming_a_sequence_outside_the_batch_is_flagged_and_contributes_not
         Vq0 = tuple(a[sel] for a in Vq)
         ref0 = G.decode_ref(q[:1], Kq0, Vq0, [sel.size])
         G.assert_close(out[:1], ref0, "sequence 0 without the malformed item's pages")
+    finally:
+        cache.close()
+
+
+def test_item_with_a_partial_slot_outside_the_workspace_is_flagged_and_writes_nothing(G):
+    """The partial of such an item cannot be stored: the status bit is raised, nothing outside the workspace is
+    touched (guard words behind it), and the sequences whose slots were all written are unaffected."""
+    q, K, V, seq_bits = G.random_case(25, [400, 200], 8, 2)
+    cache, (Kq, Vq) = G.check_append(seq_bits, K, V, 2)
+    try:
+        ref = G.decode_ref(q, Kq, Vq, [400, 200])
+        items, sip = cache.plan_decode(6)
+        for wrong in (items.shape[0], items.shape[0] + 1000, -1):
+            bad = items.copy()
+            k = int(np.nonzero(items[:, 3] == sip[1] - 1)[0][0])   # an item of sequence 0
+            bad[k, 3] = wrong
+            cache._plan = (torch.from_numpy(bad).to(G.DEV), cache._plan[1], bad, sip)
+            need = tkv.tkv_decode_workspace_bytes(cache.desc, items.shape[0], 8)
+            buf = torch.full((need + 4096,), 0x5A, dtype=torch.uint8, device=G.DEV)
+            cache.status.zero_()
+            out = cache.decode(harness.bf16_tensor(q, G.DEV), workspace=buf[:need])
+            torch.cuda.synchronize()
+            assert int(cache.status.item()) == tkv.TKV_STATUS_BAD_ITEM
+            assert bool((buf[need:] == 0x5A).all()), "bytes behind the workspace were written"
+            G.assert_close(out.cpu().numpy()[1:], ref[1:], "the sequence whose slots were all written")
     finally:
         cache.close()
 

@@ -159,6 +159,12 @@ def test_plan_decode_covers_every_page_once_and_balances_bytes(target):
     ip = np.concatenate([[0], np.cumsum(pages)]).astype(np.int32)
     items, sip = tkv.tkv_plan_decode(d, ip, n2, n4, target)
     assert sip[0] == 0 and sip[-1] == items.shape[0] and np.all(np.diff(sip) >= 0)
+    # items come in launch order; their partial slots are a permutation in sequence order
+    assert sorted(items[:, 3].tolist()) == list(range(items.shape[0]))
+    p2_of = -(-n2 // 64)
+    share2 = np.array([(min(hi, p2_of[b]) - min(lo, p2_of[b])) * 4096 // (hi - lo) for b, lo, hi, _ in items])
+    assert np.all(np.diff(share2) <= 0), "launch order: falling share of INT2 pages"
+    items = items[np.argsort(items[:, 3])]
     assert items.shape[0] <= tkv.tkv_plan_decode_capacity(B, target)
     cost = lambda b, lo, hi: 6 * (min(hi, -(-n2[b] // 64)) - min(lo, -(-n2[b] // 64))) + \
         7 * (max(hi, -(-n2[b] // 64)) - max(lo, -(-n2[b] // 64)))
