@@ -113,9 +113,11 @@ class PagedCache:
         self.seqs, self.alloc = [], None
 
     # -- Q2-Q5
-    def append(self, K: torch.Tensor, V: torch.Tensor, pool=None, stream=None):
-        tkv.tkv_quantize_append(self.desc, self.pool if pool is None else pool, self.bit_map, K, V,
-                                self.d_tag_bits, self.d_work_pages, self.d_work_src, self.status, stream)
+    def append(self, K: torch.Tensor, V: torch.Tensor, pool=None, stream=None, prepare=False):
+        """prepare=True returns the call with its arguments marshalled once (tkv.Prepared) instead of making it."""
+        return tkv.tkv_quantize_append(self.desc, self.pool if pool is None else pool, self.bit_map, K, V,
+                                       self.d_tag_bits, self.d_work_pages, self.d_work_src, self.status, stream,
+                                       prepare=prepare)
 
     # -- P1
     def gather(self, K_out: torch.Tensor, V_out: torch.Tensor, pool=None, stream=None):
@@ -130,8 +132,11 @@ class PagedCache:
         return items, sip
 
     # -- D2-D7
-    def decode(self, q: torch.Tensor, out: torch.Tensor | None = None, workspace=None, pool=None, stream=None):
+    def decode(self, q: torch.Tensor, out: torch.Tensor | None = None, workspace=None, pool=None, stream=None,
+               prepare=False):
+        """prepare=True returns the call (tkv.Prepared) instead of `out`; `out` and `workspace` must then be given."""
         assert self._plan is not None, "call plan_decode first"
+        assert not prepare or (out is not None and workspace is not None)
         d_items, d_sip, items, _ = self._plan
         B, Hq = int(q.shape[0]), int(q.shape[1])
         if out is None:
@@ -139,10 +144,10 @@ class PagedCache:
         if workspace is None:
             workspace = self.workspace(Hq)
         sm_scale = np.float32(1.0 / math.sqrt(tkv.HEAD_DIM))
-        tkv.tkv_decode_attention(self.desc, self.pool if pool is None else pool, self.bit_map, q,
-                                 self.d_page_indptr, self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items, d_sip,
-                                 float(sm_scale), out, workspace, self.status, stream)
-        return out
+        call = tkv.tkv_decode_attention(self.desc, self.pool if pool is None else pool, self.bit_map, q,
+                                        self.d_page_indptr, self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items, d_sip,
+                                        float(sm_scale), out, workspace, self.status, stream, prepare=prepare)
+        return call if prepare else out
 
     def decode_static(self, q: torch.Tensor, out: torch.Tensor, pool=None, stream=None):
         """D2-D7 with the partials in the library's fixed device array: nothing is allocated here either
@@ -154,13 +159,13 @@ class PagedCache:
                                         d_sip, float(sm_scale), out, self.status, stream)
         return out
 
-    def decode_split(self, q: torch.Tensor, workspace, pool=None, stream=None):
+    def decode_split(self, q: torch.Tensor, workspace, pool=None, stream=None, prepare=False):
         """D2-D6 only (used by the benchmark to time the split kernel by itself)."""
         d_items = self._plan[0]
         sm_scale = np.float32(1.0 / math.sqrt(tkv.HEAD_DIM))
-        tkv.tkv_decode_split(self.desc, self.pool if pool is None else pool, self.bit_map, q, self.d_page_indptr,
-                             self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items, float(sm_scale), workspace,
-                             self.status, stream)
+        return tkv.tkv_decode_split(self.desc, self.pool if pool is None else pool, self.bit_map, q, self.d_page_indptr,
+                                    self.d_page_ids, self.d_n_tok2, self.d_n_tok4, d_items, float(sm_scale), workspace,
+                                    self.status, stream, prepare=prepare)
 
     def workspace(self, n_q_heads: int) -> torch.Tensor:
         n_items = self._plan[2].shape[0]

@@ -165,6 +165,28 @@ def _stream(stream):
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
 
 
+class Prepared:
+    """One call of an entry point with its arguments marshalled once.  Loops that repeat the same call on the same
+    buffers and stream (a decode step per layer, a benchmark) pay for building the ctypes arguments only the first
+    time: `call = tkv_decode_attention(..., prepare=True)`, then `call()`.  The tensors are kept alive here."""
+    __slots__ = ("fn", "cargs", "where", "keep")
+
+    def __init__(self, fn, cargs, where, keep):
+        self.fn, self.cargs, self.where, self.keep = fn, cargs, where, keep
+
+    def __call__(self):
+        st = self.fn(*self.cargs)
+        if st < 0:
+            _check(st, self.where)
+
+
+def _run(fn, cargs, where, keep, prepare):
+    call = Prepared(fn, cargs, where, keep)
+    if prepare:
+        return call
+    call()
+
+
 # ---------------------------------------------------------------- geometry
 def tkv_record_bytes(bits: int) -> int:
     return int(lib().tkv_record_bytes(bits))
@@ -270,7 +292,7 @@ def tkv_plan_append(a, s, tag_bits, token_base: int = 0):
 
 # ---------------------------------------------------------------- Q2-Q5 (device)
 def tkv_quantize_append(desc, pool, bit_map, K, V, tag_bits, work_pages, work_src, status=None, stream=None,
-                        group_size: int = GROUP_SIZE):
+                        group_size: int = GROUP_SIZE, prepare=False):
     """All array arguments are torch device tensors: pool u8, bit_map u8,
     K/V bf16 [T,Hkv,D], tag_bits u8[T], work_pages i32[n_work], work_src i32[n_work,64]."""
     n_tokens = int(K.shape[0]) if K is not None else 0
@@ -282,9 +304,10 @@ def tkv_quantize_append(desc, pool, bit_map, K, V, tag_bits, work_pages, work_sr
         assert work_src.numel() == n_work * desc.page_tokens and work_src.element_size() == 4
         assert pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
         assert bit_map.numel() >= desc.n_pages_int2 + desc.n_pages_int4
-    _check(lib().tkv_quantize_append(C.byref(desc), _dev(pool), _dev(bit_map), _dev(K), _dev(V), _dev(tag_bits),
-                                     n_tokens, group_size, _dev(work_pages), _dev(work_src), n_work,
-                                     _dev(status), _stream(stream)), "tkv_quantize_append")
+    return _run(lib().tkv_quantize_append,
+                (C.byref(desc), _dev(pool), _dev(bit_map), _dev(K), _dev(V), _dev(tag_bits), n_tokens, group_size,
+                 _dev(work_pages), _dev(work_src), n_work, _dev(status), _stream(stream)),
+                "tkv_quantize_append", (desc, pool, bit_map, K, V, tag_bits, work_pages, work_src, status, stream), prepare)
 
 
 # ---------------------------------------------------------------- P1 (device)
@@ -331,7 +354,7 @@ def tkv_decode_workspace_bytes(desc, n_items: int, n_q_heads: int) -> int:
 
 
 def tkv_decode_attention(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items,
-                         seq_item_indptr, sm_scale: float, out, workspace, status=None, stream=None):
+                         seq_item_indptr, sm_scale: float, out, workspace, status=None, stream=None, prepare=False):
     """Device tensors: q bf16 [B,Hq,D]; page_indptr i32[B+1]; page_ids i32; n_tok_int2/4 i32[B];
     items i32[n_items,4]; seq_item_indptr i32[B+1]; out f32 [B,Hq,D]; workspace u8."""
     batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
@@ -343,11 +366,13 @@ def tkv_decode_attention(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_in
     assert out.numel() == batch * n_q_heads * desc.head_dim and out.element_size() == 4
     if n_items:
         assert items.numel() == 4 * n_items and pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
-    _check(lib().tkv_decode_attention(C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr),
-                                      _dev(page_ids), _dev(n_tok_int2), _dev(n_tok_int4), _dev(items),
-                                      _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
-                                      _dev(out), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
-           "tkv_decode_attention")
+    return _run(lib().tkv_decode_attention,
+                (C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr), _dev(page_ids), _dev(n_tok_int2),
+                 _dev(n_tok_int4), _dev(items), _dev(seq_item_indptr), n_items, batch, n_q_heads, float(sm_scale),
+                 _dev(out), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
+                "tkv_decode_attention",
+                (desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, seq_item_indptr, out, workspace,
+                 status, stream), prepare)
 
 
 TKV_DECODE_STATIC_SCRATCH_BYTES = 16 << 20
@@ -373,7 +398,7 @@ def tkv_decode_attention_static(desc, pool, bit_map, q, page_indptr, page_ids, n
 
 
 def tkv_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, sm_scale: float,
-                     workspace, status=None, stream=None):
+                     workspace, status=None, stream=None, prepare=False):
     """D2-D6 only: leaves the per-item partials in `workspace`."""
     batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
     n_items = int(items.shape[0]) if items is not None else 0
@@ -382,10 +407,12 @@ def tkv_decode_split(desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, 
     assert n_tok_int2.numel() == batch and n_tok_int4.numel() == batch
     if n_items:
         assert items.numel() == 4 * n_items and pool.numel() * pool.element_size() >= tkv_pool_bytes(desc)
-    _check(lib().tkv_decode_split(C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr), _dev(page_ids),
-                                  _dev(n_tok_int2), _dev(n_tok_int4), _dev(items), n_items, batch, n_q_heads,
-                                  float(sm_scale), _dev(workspace), ws_bytes, _dev(status), _stream(stream)),
-           "tkv_decode_split")
+    return _run(lib().tkv_decode_split,
+                (C.byref(desc), _dev(pool), _dev(bit_map), _dev(q), _dev(page_indptr), _dev(page_ids), _dev(n_tok_int2),
+                 _dev(n_tok_int4), _dev(items), n_items, batch, n_q_heads, float(sm_scale), _dev(workspace), ws_bytes,
+                 _dev(status), _stream(stream)),
+                "tkv_decode_split",
+                (desc, pool, bit_map, q, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, workspace, status, stream), prepare)
 
 
 def tkv_decode_reduce(desc, seq_item_indptr, n_items: int, out, workspace, stream=None):
