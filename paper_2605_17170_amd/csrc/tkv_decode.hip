@@ -423,8 +423,9 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     }
     lds_order();
 
-    // ---- QK^T: S[e][i] = q . k_hat (unscaled) for token 16e + 4*q4 + i, head column r16
-    floatx4 S[4];   // per-channel keys: tile e; else blocks 0, 1 only
+    // ---- QK^T: S[blk][i] = q . k_hat (unscaled) of token 32*blk + 16*(r16 >> 3) + 4*q4 + i for the head of column
+    // r16 (two token sets); the per-channel path works on the four 16-token tiles first and folds them at its end
+    floatx4 S[4];
     if constexpr (kPerChannel) {
         // score = sum_c (q_c s_c) code + sum_c q_c z_c with s, z of the token's block.  q s is formed per block
         // in two fp16 pieces, exactly (q has 8 significant bits, s 11): head columns 0..7 take
@@ -470,6 +471,11 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             for (int i = 0; i < 4; ++i) S[e][i] += row_ror8(S[e][i]);   // the two pieces of q s: columns h and h + 8
             asm volatile("" : "+v"(S[e]));
         }
+        // Both column halves now hold the logits of all four tiles.  From here on the page is treated as with
+        // per-token keys: columns 0..7 go on with tile 2*blk, columns 8..15 with tile 2*blk + 1 (two token sets), so
+        // that exponentials and weight pieces are formed once per (token, head).
+        if (r16 >= 8) { S[0] = S[1]; S[2] = S[3]; }
+        S[1] = S[2];
         __builtin_amdgcn_sched_barrier(0);
     } else {
         // Per-token groups.  The eight heads fill only half of the 16 MFMA columns, so the columns carry two
@@ -519,13 +525,13 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         }
     }
     after_qk();
-    constexpr int kS = kPerChannel ? 4 : 2;   // logit registers of this lane: 16 tokens (every column half the same) or 8
+    constexpr int kS = 2;   // logit registers of this lane: its eight tokens of the page
     if (partial) {
 #pragma unroll
         for (int e = 0; e < kS; ++e)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int t = kPerChannel ? 16 * e + 4 * q4 + i : 32 * e + lc.tok0 + i;
+                const int t = 32 * e + lc.tok0 + i;
                 S[e][i] = t < n_valid ? S[e][i] : -INFINITY;
             }
     }
@@ -537,7 +543,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 #pragma unroll
     for (int e = 1; e < kS; ++e) mx = fmaxf(fmaxf(mx, S[e][0]), fmaxf(fmaxf(S[e][1], S[e][2]), S[e][3]));
     if (__any(mx * lc.kappa > st.m_ref + kTau)) {
-        if constexpr (!kPerChannel) mx = fmaxf(mx, row_ror8(mx));   // the other token set of the head
+        mx = fmaxf(mx, row_ror8(mx));   // the other token set of the head
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(st.m_ref, mx * lc.kappa);
@@ -567,15 +573,10 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pv[2 * k], pv[2 * k + 1]));
             const uint32_t lo = __builtin_bit_cast(
                 uint32_t, __builtin_amdgcn_cvt_pkrtz(residual<0>(hi, -1.0f, pv[2 * k]), residual<1>(hi, -1.0f, pv[2 * k + 1])));
-            if constexpr (kPerChannel) {
-                wh[e >> 1][2 * (e & 1) + k] = hi;
-                wl[e >> 1][2 * (e & 1) + k] = lo;
-            } else {
-                wh[e][k] = hi;
-                wl[e][k] = lo;
-                wh[e][2 + k] = ror8_u32(hi);
-                wl[e][2 + k] = ror8_u32(lo);
-            }
+            wh[e][k] = hi;
+            wl[e][k] = lo;
+            wh[e][2 + k] = ror8_u32(hi);
+            wl[e][2 + k] = ror8_u32(lo);
         }
     }
 
@@ -700,17 +701,16 @@ __device__ __forceinline__ void run_pages(const ItemCtx &cx, const WidthRange &w
         const uint32_t h01 = (uint32_t)(15 + kVExp - p01) << 10, h23 = (uint32_t)(15 + kVExp - p23) << 10;
         lc.vmul01 = h01 | (h01 << 16);
         lc.vmul23 = h23 | (h23 << 16);
-        // Order of the eight tokens of a k-slot octet in the PV operands.  Per-channel INT2 keys: every lane lists
-        // the tokens of tile 2*blk first.  Two token sets: a lane lists its own set first, which for columns 8..15
-        // (the rows and columns of groups 2 and 3) is tile 2*blk + 1: those lanes swap the register pairs of the V
-        // operand, and the staged scales of groups 2 and 3 are stored with their 8-byte halves swapped.
-        const bool swap = !(KC && BITS == 2) && (lane & 8);
+        // Order of the eight tokens of a k-slot octet in the PV operands: a lane lists its own token set first, which
+        // for columns 8..15 (the rows and columns of groups 2 and 3) is tile 2*blk + 1: those lanes swap the register
+        // pairs of the V operand, and the staged scales of groups 2 and 3 are stored with their 8-byte halves swapped.
+        const bool swap = lane & 8;
         lc.vrot[0] = swap ? 5u : 29u;   // w >> 5 / w << 3 (stray bits fall outside the masks)
         lc.vrot[1] = swap ? 29u : 5u;
         const uint32_t m[4] = {0x00180018u, 0x00600060u, 0x01800180u, 0x06000600u};
 #pragma unroll
         for (int k = 0; k < 4; ++k) lc.vmask[k] = m[swap ? k ^ 2 : k];
-        lc.vs_st = !(KC && BITS == 2) && (lane & 4) ? lane ^ 1 : lane;   // lane = ((blk*4 + quad)*4 + g)*2 + half
+        lc.vs_st = (lane & 4) ? lane ^ 1 : lane;   // lane = ((blk*4 + quad)*4 + g)*2 + half
     }
     // One register set: every part of the next record is requested as soon as the registers it lands in
     // are dead, so about one page per wavefront is in flight while the current one is computed.
