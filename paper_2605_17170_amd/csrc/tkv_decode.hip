@@ -183,7 +183,8 @@ struct WaveState {
 constexpr int kQyStride = 17, kQyZero = 16;
 constexpr int kPvZ = 0, kPvS = 32, kPvZero = 64, kPvOne = 65, kPvChunks = 66;
 
-// Only the kernel for per-channel INT2 keys holds the second q operand.
+// What only one of the two kernels keeps in LDS: the staged q (per-token keys; the other kernel borrows the page
+// staging area for it), the second q operand (per-channel INT2 keys).
 template <bool KC> struct LdsExtra {
     alignas(16) _Float16 qf[8][kHeadDim + 8];            // q * 2^E per head and channel (qf_chunk), kept for the whole item
 };
@@ -637,8 +638,8 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     after_pv();
 }
 
-// All pages [pb, pe) of one width (indices into the sequence's page list).
-// What stays the same for every page of a work item, and the pages of one width in it.
+// What stays the same for every page of a work item, and the pages of one width in it (positions in the
+// sequence's page list).
 struct ItemCtx {
     const uint8_t *__restrict__ pool;
     const uint8_t *__restrict__ bit_map;
