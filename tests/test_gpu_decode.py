@@ -275,6 +275,17 @@ def test_item_with_a_partial_slot_outside_the_workspace_is_flagged_and_writes_no
         cache.close()
 
 
+def test_many_short_sequences_more_items_than_fit_the_device(G):
+    """700 sequences of 1..200 tokens (some empty) on 8 kv heads: more (item, head) workgroups than the device
+    holds at once whatever the target, so late workgroups start when early ones end; one item per sequence."""
+    rng = np.random.default_rng(31)
+    seq_lens = rng.integers(1, 200, 700).tolist()
+    for k in (5, 333, 699):
+        seq_lens[k] = 0
+    q, K, V, seq_bits = G.random_case(31, seq_lens, 8, 8)
+    _run(G, q, K, V, seq_bits, 8, 8, targets=(1, 384))
+
+
 def test_cfg1(G):
     w = wl.config("cfg1")
     q, K, V, _ = w.make_inputs()
