@@ -208,12 +208,26 @@ def append_leg(name, steps=5, warmup=2):
     gper, _ = timed(lambda i: cache.gather(gK, gV), steps, warmup)
     gms = float(np.median(gper))
     assert int(cache.status.item()) == 0
+    # ceilings for these byte mixes: plain streams that read 4 bytes per byte written (append) and the reverse (gather)
+    from paper_2605_17170_amd import tkv
+    unit = (wr // 16) * 16
+    src = K.view(torch.uint8).reshape(-1)
+    big = torch.empty(4 * unit, dtype=torch.uint8, device=dev)
+    mix41 = tkv.tkv_probe_stream_mix(big, cache.pool, unit, 4, 1, prepare=True)
+    mix14 = tkv.tkv_probe_stream_mix(cache.pool, big, unit, 1, 4, prepare=True)
+    m41 = float(np.median(timed(lambda i: mix41(), steps, warmup)[0]))
+    m14 = float(np.median(timed(lambda i: mix14(), steps, warmup)[0]))
+    del big, src
     res = {"workload": "%s: %d new bf16 K and V tokens, %d kv heads, INT4 token share %.2f, randomly allocated pages"
                        % (name, w.n_tokens, w.n_kv_heads, w.f4()),
            "append_ms": ms, "tokens_per_s": w.n_tokens / (ms * 1e-3), "GBps_read_plus_write": (rd + wr) / (ms * 1e-3) / 1e9,
            "frac_of_hbm_peak": frac(rd + wr, ms), "bytes_read": rd, "bytes_written": wr,
            "prefill_gather_ms": gms, "prefill_gather_GBps_read_plus_write": (wr + 2 * gK.numel() * 2) / (gms * 1e-3) / 1e9,
-           "prefill_gather_frac_of_hbm_peak": frac(wr + 2 * gK.numel() * 2, gms)}
+           "prefill_gather_frac_of_hbm_peak": frac(wr + 2 * gK.numel() * 2, gms),
+           "stream_read4_write1_GBps": 5 * unit / (m41 * 1e-3) / 1e9, "stream_read1_write4_GBps": 5 * unit / (m14 * 1e-3) / 1e9,
+           "ceiling_note": "tkv_probe_stream_mix: plain 128-bit streams of the same size in the byte ratio of the append "
+                           "(reads 4, writes 1) and of the gather (reads 1, writes 4); the second one overwrites the pool, "
+                           "after the measurements that needed it"}
     cache.close()
     return res
 
@@ -248,6 +262,16 @@ def main():
     stream_read = cache.pool_bytes / (float(np.mean(probe)) * 1e-3) / 1e9
     kv_layer, kv_step = main_res["kv_bytes_per_layer"], main_res["kv_bytes_per_step"]
     kernel_us = main_res["kernel_us"]
+    # the decode kernel's own reads without its arithmetic: records fetched one per wavefront at a time, first with
+    # computed addresses (what the memory system gives this access pattern), then through the item and page tables as
+    # the kernel does (its memory skeleton, start-up chain and ragged end included)
+    d_items = cache._plan[0]
+    rec_calls = {walk: [tkv.tkv_probe_decode_reads(cache.desc, p_, cache.d_page_indptr, cache.d_page_ids, cache.d_n_tok2,
+                                                   cache.d_n_tok4, d_items, w.batch, walk, prepare=True) for p_ in pools]
+                 for walk in (False, True)}
+    rec_t = {walk: float(np.mean(timed(lambda i: rec_calls[walk][i % len(pools)](), 40, 5)[0])) for walk in (False, True)}
+    record_read = cache.pool_bytes / (rec_t[False] * 1e-3) / 1e9
+    skeleton = kv_layer / (rec_t[True] * 1e-3) / 1e9
     res = {
         "metric": METRIC, "value": main_res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": main_res["ms_per_step"], "us_per_decode_step": main_res["ms_per_step"] * 1e3,
@@ -265,12 +289,16 @@ def main():
                      "traffic": read_traffic("decode_%s_hbm_traffic.txt" % head),
                      "kernel": "tkv_decode_kernel", "kernel_us": kernel_us, "bytes_per_launch": kv_layer,
                      "stream_read_GBps": stream_read, "frac_of_stream_read": kv_layer / (kernel_us * 1e-6) / 1e9 / stream_read,
+                     "record_read_GBps": record_read, "memory_skeleton_GBps": skeleton, "memory_skeleton_us": rec_t[True] * 1e3,
                      "csrc_sha": csrc_hash(),
                      "note": "tkv_decode_kernel launched by itself (tkv_decode_split) over the same pools in the same order, mean "
                              "interval per launch from HIP events around the timed launches on the launch stream; algorithmic bytes "
                              "per launch = 96 B/INT2 token + 160 B/INT4 token per kv head of one layer; traffic = HBM bytes per launch "
                              "from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), null unless that summary was taken from these kernel "
-                             "sources; stream_read_GBps = a plain 128-bit streaming read of the same pools (tkv_probe_stream_read)"},
+                             "sources; stream_read_GBps = a plain 128-bit streaming read of the same pools (tkv_probe_stream_read); "
+                             "record_read_GBps = the pool's records read whole, one per wavefront at a time, addresses computed; "
+                             "memory_skeleton = the same reads through the items and page tables, i.e. the decode kernel without "
+                             "its arithmetic (tkv_probe_decode_reads, walk = 0 / 1)"},
     }
     if not args.no_cpu:
         # the oracle on a bounded sample: the leading sequences of layer 0 (device-generated K/V copied to the host)

@@ -434,6 +434,34 @@ int tkv_decode_attention_static(const tkv_desc *desc, const void *pool, const ui
  * misaligned buffer.
  */
 int tkv_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *stream /* hipStream_t */);
+/*
+ * Fetches the records that a decode plan reads, in the decode kernel's own
+ * decomposition (Sec. 3.2.3, "Decode": one wavefront per (work item, kv head),
+ * whole records, the next one requested when the current one has arrived) and
+ * discards them: what the memory system delivers to that access pattern, with
+ * none of the arithmetic.
+ *   walk = 1  addresses come from the items and the device page tables exactly
+ *             as in tkv_decode_split (same arguments, same meaning): the
+ *             kernel's memory skeleton, start-up chain included;
+ *   walk = 0  wavefront w of the n_items * n_kv_heads reads records w, w + W,
+ *             ... of the whole pool, addresses computed; the page tables and
+ *             items are not read (may be NULL).
+ * sink as for tkv_probe_stream_read.  n_items = 0 or an empty pool is a no-op.
+ */
+int tkv_probe_decode_reads(const tkv_desc *desc, const void *pool, const int32_t *page_indptr,
+                           const int32_t *page_ids, const int32_t *n_tok_int2, const int32_t *n_tok_int4,
+                           const int32_t *items, int32_t n_items, int32_t batch, int32_t walk,
+                           uint32_t *sink, void *stream /* hipStream_t */);
+/*
+ * Streams read_parts * unit_bytes out of `src` and writes write_parts *
+ * unit_bytes into `dst` (device, 16-byte aligned, unit_bytes a multiple of 16)
+ * with 128-bit accesses: the ceiling of the device for a kernel that reads and
+ * writes in that byte ratio.  Supported ratios: 4 : 1 (tkv_quantize_append reads
+ * 512 B of bf16 per 96..160 B it writes), 1 : 4 (tkv_gather_dequant), 1 : 1.
+ * What is written is a fold of what was read.  unit_bytes = 0 is a no-op.
+ */
+int tkv_probe_stream_mix(const void *src, void *dst, size_t unit_bytes, int32_t read_parts,
+                         int32_t write_parts, void *stream /* hipStream_t */);
 
 #ifdef __cplusplus
 }

@@ -471,6 +471,30 @@ int tkv_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *s
     return tkv_launch_probe_read(buf, bytes, sink, stream);
 }
 
+int tkv_probe_decode_reads(const tkv_desc *desc, const void *pool, const int32_t *page_indptr, const int32_t *page_ids,
+                           const int32_t *n_tok_int2, const int32_t *n_tok_int4, const int32_t *items, int32_t n_items,
+                           int32_t batch, int32_t walk, uint32_t *sink, void *stream)
+{
+    if (int st = desc_status(desc)) return st;
+    if (n_items < 0 || batch < 0 || (walk != 0 && walk != 1)) return TKV_ERR_INVALID_ARG;
+    if ((int64_t)n_items * desc->n_kv_heads > INT32_MAX) return TKV_ERR_INVALID_ARG;
+    if (n_items == 0 || desc->n_pages_int2 + desc->n_pages_int4 == 0) return TKV_OK;
+    if (!pool || ((uintptr_t)pool & 255)) return TKV_ERR_INVALID_ARG;
+    if (walk && (batch == 0 || !page_indptr || !page_ids || !n_tok_int2 || !n_tok_int4 || !items)) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_probe_records(desc, pool, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, n_items, batch, walk,
+                                    sink, stream);
+}
+
+int tkv_probe_stream_mix(const void *src, void *dst, size_t unit_bytes, int32_t read_parts, int32_t write_parts, void *stream)
+{
+    const bool known = (read_parts == 4 && write_parts == 1) || (read_parts == 1 && write_parts == 4) ||
+                       (read_parts == 1 && write_parts == 1);
+    if (!known || (unit_bytes & 15)) return TKV_ERR_INVALID_ARG;
+    if (unit_bytes == 0) return TKV_OK;
+    if (!src || !dst || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return TKV_ERR_INVALID_ARG;
+    return tkv_launch_probe_mix(src, dst, unit_bytes / 16, read_parts, write_parts, stream);
+}
+
 namespace {
 int alloc_args_status(int32_t n_tags, const int64_t *N, const double *D2, const double *D4, double B, const uint8_t *out)
 {

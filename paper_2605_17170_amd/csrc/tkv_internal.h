@@ -16,6 +16,10 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
                       int32_t *status, void *stream);
 
 int tkv_launch_probe_read(const void *buf, size_t bytes, uint32_t *sink, void *stream);
+int tkv_launch_probe_records(const tkv_desc *desc, const void *pool, const int32_t *page_indptr, const int32_t *page_ids,
+                             const int32_t *n_tok_int2, const int32_t *n_tok_int4, const int32_t *items, int32_t n_items,
+                             int32_t batch, int32_t walk, uint32_t *sink, void *stream);
+int tkv_launch_probe_mix(const void *src, void *dst, size_t n_units, int32_t read_parts, int32_t write_parts, void *stream);
 
 int tkv_launch_decode_split(const tkv_desc *desc, const void *pool, const uint8_t *bit_map, const void *q,
                             const int32_t *page_indptr, const int32_t *page_ids, const int32_t *n_tok_int2,

@@ -44,6 +44,7 @@ EXPORTS = [
     "tkv_plan_decode_capacity", "tkv_plan_decode", "tkv_decode_workspace_bytes", "tkv_decode_attention",
     "tkv_decode_split", "tkv_decode_reduce", "tkv_decode_attention_static", "tkv_allocate_bits_greedy", "tkv_allocate_bits_exhaustive",
     "tkv_tag_tokens", "tkv_tags_to_bits", "tkv_tag_counts", "tkv_probe_stream_read",
+    "tkv_probe_decode_reads", "tkv_probe_stream_mix",
 ]
 
 
@@ -124,6 +125,8 @@ def lib():
         L.tkv_decode_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, sz, vp, vp]
         L.tkv_decode_reduce.argtypes = [dp, vp, i32, i32, i32, vp, vp, sz, vp]
         L.tkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.tkv_probe_decode_reads.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+        L.tkv_probe_stream_mix.argtypes = [vp, vp, sz, i32, i32, vp]
         L.tkv_tag_tokens.argtypes = [vp, vp, i32, vp]
         L.tkv_tags_to_bits.argtypes = [vp, i32, vp, vp]
         L.tkv_tag_counts.argtypes = [vp, i32, vp]
@@ -482,3 +485,21 @@ def tkv_probe_stream_read(buf, stream=None):
     nbytes = buf.numel() * buf.element_size()
     _check(lib().tkv_probe_stream_read(_dev(buf), nbytes - nbytes % 16, C.c_void_p(None), _stream(stream)),
            "tkv_probe_stream_read")
+
+
+def tkv_probe_decode_reads(desc, pool, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, batch: int, walk: bool,
+                           stream=None, prepare=False):
+    """The record reads of a decode plan without the arithmetic (device tensors as for tkv_decode_split)."""
+    n_items = int(items.shape[0]) if items is not None else 0
+    return _run(lib().tkv_probe_decode_reads,
+                (C.byref(desc), _dev(pool), _dev(page_indptr), _dev(page_ids), _dev(n_tok_int2), _dev(n_tok_int4), _dev(items),
+                 n_items, batch, 1 if walk else 0, C.c_void_p(None), _stream(stream)),
+                "tkv_probe_decode_reads", (desc, pool, page_indptr, page_ids, n_tok_int2, n_tok_int4, items, stream), prepare)
+
+
+def tkv_probe_stream_mix(src, dst, unit_bytes: int, read_parts: int, write_parts: int, stream=None, prepare=False):
+    """Streaming read of read_parts * unit_bytes of `src` and write of write_parts * unit_bytes of `dst`."""
+    assert src.numel() * src.element_size() >= read_parts * unit_bytes
+    assert dst.numel() * dst.element_size() >= write_parts * unit_bytes
+    return _run(lib().tkv_probe_stream_mix, (_dev(src), _dev(dst), unit_bytes, read_parts, write_parts, _stream(stream)),
+                "tkv_probe_stream_mix", (src, dst, stream), prepare)

@@ -14,6 +14,9 @@ int tkv_launch_append(const tkv_desc *, void *, uint8_t *, const void *, const v
 int tkv_launch_gather(const tkv_desc *, const void *, const uint8_t *, const int32_t *, const int32_t *, int32_t, void *,
                       void *, int32_t, int32_t *, void *) { return TKV_OK; }
 int tkv_launch_probe_read(const void *, size_t, uint32_t *, void *) { return TKV_OK; }
+int tkv_launch_probe_records(const tkv_desc *, const void *, const int32_t *, const int32_t *, const int32_t *, const int32_t *,
+                             const int32_t *, int32_t, int32_t, int32_t, uint32_t *, void *) { return TKV_OK; }
+int tkv_launch_probe_mix(const void *, void *, size_t, int32_t, int32_t, void *) { return TKV_OK; }
 int tkv_launch_decode_split(const tkv_desc *, const void *, const uint8_t *, const void *, const int32_t *, const int32_t *,
                             const int32_t *, const int32_t *, const int32_t *, int32_t, int32_t, int32_t, float, void *,
                             int32_t *, void *) { return TKV_OK; }

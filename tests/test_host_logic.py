@@ -317,6 +317,29 @@ def test_per_channel_key_mode_is_validated():
     tkv.tkv_alloc_destroy(a)
 
 
+def test_record_and_mix_probes_validate_before_launch():
+    L = tkv.lib()
+    d = tkv.tkv_desc.make(8, 4, 4)
+    fake, null = C.c_void_p(0x1000), C.c_void_p(None)
+    rec = lambda **kw: L.tkv_probe_decode_reads(C.byref(kw.get("desc", d)), kw.get("pool", fake), fake, fake, fake, fake,
+                                                kw.get("items", fake), kw.get("n_items", 4), kw.get("batch", 2), kw.get("walk", 1),
+                                                null, null)
+    assert rec(n_items=0) == tkv.TKV_OK
+    assert rec(desc=tkv.tkv_desc.make(8, 0, 0)) == tkv.TKV_OK                      # an empty pool: nothing to read
+    assert rec(desc=tkv.tkv_desc.make(8, 4, 4, head_dim=64)) == tkv.TKV_ERR_BAD_SHAPE
+    assert rec(n_items=-1) == tkv.TKV_ERR_INVALID_ARG
+    assert rec(walk=2) == tkv.TKV_ERR_INVALID_ARG
+    assert rec(pool=null) == tkv.TKV_ERR_INVALID_ARG
+    assert rec(pool=C.c_void_p(0x1010)) == tkv.TKV_ERR_INVALID_ARG
+    assert rec(items=null) == tkv.TKV_ERR_INVALID_ARG                            # walk = 1 reads the items
+    assert rec(batch=0) == tkv.TKV_ERR_INVALID_ARG
+    mix = lambda src=fake, dst=fake, n=64, r=4, w=1: L.tkv_probe_stream_mix(src, dst, n, r, w, null)
+    assert mix(n=0) == tkv.TKV_OK
+    assert mix(r=3) == tkv.TKV_ERR_INVALID_ARG and mix(r=1, w=2) == tkv.TKV_ERR_INVALID_ARG
+    assert mix(n=24) == tkv.TKV_ERR_INVALID_ARG
+    assert mix(src=null) == tkv.TKV_ERR_INVALID_ARG and mix(dst=C.c_void_p(0x1008)) == tkv.TKV_ERR_INVALID_ARG
+
+
 def test_stream_read_probe_validates_before_launch():
     L = tkv.lib()
     assert L.tkv_probe_stream_read(None, 0, None, None) == tkv.TKV_OK                 # nothing to read
