@@ -400,8 +400,15 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             reinterpret_cast<uint2 *>(lds.kc_zero())[lane] = kz;
         } else {
             const half2_t a = __builtin_bit_cast(half2_t, pr.ksc.x), b = __builtin_bit_cast(half2_t, pr.ksc.y);
-            reinterpret_cast<float4 *>(lds.ks)[lane] =
-                make_float4((float)a[0] * lc.F, (float)a[1] * lc.F, (float)b[0] * lc.F, (float)b[1] * lc.F);
+            // K scale * F as fp32 [block][group][token of the block]: a lane reads the scales of its four tokens for
+            // one group with one 16-byte read
+            {
+                float *kst = lds.ks + (lane >> 5) * 128 + (lane & 31);
+                kst[0] = (float)a[0] * lc.F;
+                kst[32] = (float)a[1] * lc.F;
+                kst[64] = (float)b[0] * lc.F;
+                kst[96] = (float)b[1] * lc.F;
+            }
             // K zeros: lane (r, q4) takes those of token 32*blk + 16*(q4 >> 1) + r, which lane number that token holds.
             // An MFMA row holds a token of either set: a never-written token's zero-point (any bit pattern) would
             // meet the zeros of the other set's columns in the same row and could make them NaN.
@@ -486,18 +493,22 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         // of its k-slots and zeros in the other.  All that follows the MFMAs (K scale, exponentials, weight
         // pieces) is then done once per (token, head).
         const uint4 *qy = reinterpret_cast<const uint4 *>(lds.qo);
+        floatx4 s[2];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].x, kzv[blk].y);
-            floatx4 s = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
-            float4 sc[4];
+            s[blk] = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
+        }
+        // group by group, both 32-token blocks against one read of the q operand: two independent MFMA chains
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sc[i] = reinterpret_cast<const float4 *>(lds.ks)[32 * blk + lc.tok0 + i];
+        for (int g = 0; g < 4; ++g) {
+            floatx4 p[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                floatx4 p = {0.f, 0.f, 0.f, 0.f};
+            for (int hg = 0; hg < 2; ++hg) {
+                const uint4 qb4 = qy[(g * 2 + hg) * kQyStride + lc.qy_ent];
+                const half8 qb = as_half8(qb4.x, qb4.y, qb4.z, qb4.w);
 #pragma unroll
-                for (int hg = 0; hg < 2; ++hg) {
+                for (int blk = 0; blk < 2; ++blk) {
                     const uint4 kw = pr.kw[blk * 2 + hg];
                     const uint32_t w = g == 0 ? kw.x : g == 1 ? kw.y : g == 2 ? kw.z : kw.w;
                     half8 a;
@@ -511,19 +522,22 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
                         const uint32_t ws = __builtin_amdgcn_alignbit(w, w, (q4 & 1) ? 5u : 29u);
                         a = as_half8(ws & 0x00180018u, ws & 0x00600060u, ws & 0x01800180u, ws & 0x06000600u);
                     }
-                    const uint4 qb = qy[(g * 2 + hg) * kQyStride + lc.qy_ent];
-                    p = mfma(a, as_half8(qb.x, qb.y, qb.z, qb.w), p);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float scg = g == 0 ? sc[i].x : g == 1 ? sc[i].y : g == 2 ? sc[i].z : sc[i].w;
-                    s[i] = fmaf(scg, p[i], s[i]);
+                    p[blk] = mfma(a, qb, p[blk]);
                 }
             }
-            asm volatile("" : "+v"(s));   // the scaled sums are formed here, not sunk next to their first use
-            S[blk] = s;
-            __builtin_amdgcn_sched_barrier(0);   // one block's LDS operands at a time (register pressure)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                const float4 sc = reinterpret_cast<const float4 *>(lds.ks)[(blk * 4 + g) * 8 + (lc.tok0 >> 2)];
+                s[blk][0] = fmaf(sc.x, p[blk][0], s[blk][0]);
+                s[blk][1] = fmaf(sc.y, p[blk][1], s[blk][1]);
+                s[blk][2] = fmaf(sc.z, p[blk][2], s[blk][2]);
+                s[blk][3] = fmaf(sc.w, p[blk][3], s[blk][3]);
+            }
         }
+        S[0] = s[0];
+        S[1] = s[1];
+        asm volatile("" : "+v"(S[0]), "+v"(S[1]));   // the scaled sums are formed here, not sunk next to their first use
+        __builtin_amdgcn_sched_barrier(0);
     }
     after_qk();
     constexpr int kS = 2;   // logit registers of this lane: its eight tokens of the page
