@@ -52,7 +52,8 @@ enum {
     TKV_STATUS_BLOCK_PARTIAL = 16,   /* append, per-channel INT2 keys: a 32-token block arrived incomplete (block skipped) */
     TKV_STATUS_SCALE_SATURATED = 32, /* decode: a stored V scale above 255, or a per-channel INT2 key scale above 1023, was
                                         clamped: the output is finite but not the attention over the stored values */
-    TKV_STATUS_BAD_ITEM = 64         /* decode: a work item names a sequence outside the batch (it contributes nothing) */
+    TKV_STATUS_BAD_ITEM = 64         /* decode: a work item names a sequence outside the batch (it contributes nothing)
+                                        or a partial slot outside the workspace (its partial is not stored) */
 };
 
 const char *tkv_strerror(int status);
