@@ -179,8 +179,11 @@ struct WaveState {
     float m_ref;        // reference maximum of this lane's head column, log2 units, -inf before the first page
 };
 
-// q operands of the QK^T MFMAs with two token sets: per (group, half group) 16 entries (sub*8 + head) and one of zeros
-constexpr int kQyStride = 17, kQyZero = 16;
+// q operands of the QK^T MFMAs with two token sets: per (group, half group) 16 entries (sub*8 + head) and two entries of
+// zeros.  The 16 lanes that a 16-byte LDS read serves together hold eight lanes that read their own entries
+// sub*8 .. sub*8+7 (32 consecutive banks) and eight that read zeros: the zero entry they use lies in the other 32
+// banks (entry 16 for sub = 1, entry 24 for sub = 0; entries 17..23 are padding).
+constexpr int kQyStride = 25, kQyZero0 = 24, kQyZero1 = 16;
 constexpr int kPvZ = 0, kPvS = 32, kPvZero = 64, kPvOne = 65, kPvChunks = 66;
 
 // What only one of the two kernels keeps in LDS: the staged q (per-token keys; the other kernel borrows the page
@@ -284,7 +287,7 @@ __device__ __forceinline__ void build_q_operand(const void *qf /* the staged q (
                 }
                 qy[(g * 2 + hg) * kQyStride + ent] = make_uint4(r[0], r[1], r[2], r[3]);
             }
-        if (lane < 8) qy[lane * kQyStride + kQyZero] = make_uint4(0u, 0u, 0u, 0u);
+        if (lane < 16) qy[(lane & 7) * kQyStride + (lane < 8 ? kQyZero0 : kQyZero1)] = make_uint4(0u, 0u, 0u, 0u);
     }
 }
 
@@ -357,7 +360,7 @@ struct LaneConst {
     uint32_t vmask[4];    // INT2 V unpack: field masks of operand registers 0..3
     int opaque_zero;      // 0, opaque to the compiler
     int tok0;             // two token sets: first token of this lane's four within a 32-token block
-    int qy_ent;           // ... entry of this lane in a q operand of the QK^T MFMAs (kQyZero: the zero entry)
+    int qy_ent;           // ... entry of this lane in a q operand of the QK^T MFMAs (or one of the two zero entries)
     float zmul;           // per-channel INT2 keys: 2^-24 in head columns 0..7, 0 in columns 8..15
 };
 
@@ -860,7 +863,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(TKV_WAVES_PE
     lc.vrot[0] = lc.vrot[1] = 0;
     lc.vmask[0] = lc.vmask[1] = lc.vmask[2] = lc.vmask[3] = 0;
     lc.tok0 = 16 * (r16 >> 3) + 4 * q4;
-    lc.qy_ent = (r16 >> 3) == (q4 >> 1) ? (q4 & 1) * 8 + (r16 & 7) : kQyZero;
+    lc.qy_ent = (r16 >> 3) == (q4 >> 1) ? (q4 & 1) * 8 + (r16 & 7) : ((q4 & 1) ? kQyZero1 : kQyZero0);
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
         lc.zp_idx[blk] = r16 < 4 ? kPvZ + (blk * 4 + q4) * 4 + r16 : (r16 == 4 ? kPvOne : kPvZero);
