@@ -302,7 +302,7 @@ def main():
     }
     if not args.no_cpu:
         # the oracle on a bounded sample: the leading sequences of layer 0 (device-generated K/V copied to the host)
-        budget_tok = max(1, 4_000_000 // w.n_kv_heads)
+        budget_tok = max(1, 8_000_000 // w.n_kv_heads)   # a whole layer of cfg5 (877 779 tokens on 8 kv heads)
         ip = w.seq_indptr
         nseq = 1
         while nseq < w.batch and ip[nseq + 1] <= budget_tok:
