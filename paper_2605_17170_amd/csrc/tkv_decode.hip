@@ -339,14 +339,14 @@ __device__ __forceinline__ void load_page_k(PageRegs<BITS> &pr, const uint8_t *_
 {
     const uint4 *kc = reinterpret_cast<const uint4 *>(rec + Rec<BITS>::kKCodes);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) pr.kw[i] = kc[kcode_chunk<BITS, KC>(i, lane)];
+    for (int i = 0; i < 4; ++i) pr.kw[i] = load_once(kc + kcode_chunk<BITS, KC>(i, lane));
 }
 template <int BITS>
 __device__ __forceinline__ void load_page_v(PageRegs<BITS> &pr, const uint8_t *__restrict__ rec, int lane)
 {
     const uint4 *vc = reinterpret_cast<const uint4 *>(rec + Rec<BITS>::kVCodes);
 #pragma unroll
-    for (int i = 0; i < BITS; ++i) pr.vw[i] = vc[vcode_chunk<BITS>(i, lane)];
+    for (int i = 0; i < BITS; ++i) pr.vw[i] = load_once(vc + vcode_chunk<BITS>(i, lane));
 }
 // Lane constants of the page loop.
 struct LaneConst {

@@ -52,5 +52,16 @@ __host__ __device__ inline int kcmeta_index(int blk, int c)
     return ((((blk * 4 + g) * 4 + quarter) << 3) + 2 * (r & 3) + ((r & 15) >> 3));
 }
 
+// A 16-byte load of data that is read once (the records of the packed cache: every byte is used once per call).
+// Non-temporal: on MI355X a plain 800 MB read runs at 7.0 TB/s with such loads and at 6.3 TB/s with ordinary
+// ones.  Only where one load instruction of a wavefront covers whole 128-byte lines: a line shared with a later
+// instruction would be fetched again.
+__device__ __forceinline__ uint4 load_once(const uint4 *p)
+{
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 } // namespace tkv
 #endif

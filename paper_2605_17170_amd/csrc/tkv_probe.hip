@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void tkv_probe_read_kernel(const uint4 *__rest
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     for (; i < n; i += stride) {
-        const uint4 v = buf[i];
+        const uint4 v = load_once(buf + i);
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     // keeps the loads alive; a lane's xor of its share hits this value once in 2^32
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(64) void tkv_probe_records_kernel(
         const bool wide = page >= n_pages_int2;
 #pragma unroll
         for (int i = 0; i < 10; ++i)
-            if (i < 6 || wide) r[i] = rec[i * 64 + lane];
+            if (i < 6 || wide) r[i] = load_once(rec + i * 64 + lane);
     };
     auto fold_record = [&](int page, const uint4 (&r)[10]) {
         const bool wide = page >= n_pages_int2;
