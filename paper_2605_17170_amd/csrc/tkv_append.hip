@@ -8,7 +8,7 @@
 // the token bound for that slot, for K and for V, entirely in registers: a
 // group is 64 contiguous bytes of the input, so min/max need no cross-lane
 // step.  K words go straight to HBM (a wavefront's stores for one word index
-// are 256 contiguous bytes).  V codes are transposed through LDS, because
+// are 256 contiguous bytes, written with non-temporal stores).  V codes are transposed through LDS, because
 // the V plane packs tokens, not channels, into a word.
 //
 // Arithmetic is IEEE binary32 without fused multiply-add so that the codes,
@@ -138,10 +138,11 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
             const GroupQ kq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(K + e));
             uint32_t *kc = reinterpret_cast<uint32_t *>(rec + R::kKCodes);
             constexpr int words = BITS;   // 32-bit words of codes per group: 4 (INT4) or 2 (INT2)
+            // these stores of a wavefront fill whole lines (256 contiguous bytes per word index, 128 per plane)
 #pragma unroll
-            for (int w = 0; w < words; ++w) kc[((tile * words + w) * 16 + row) * 4 + g] = kq.words[w];
-            reinterpret_cast<uint16_t *>(rec + R::kKScale)[slot * 4 + g] = kq.scale;
-            reinterpret_cast<uint16_t *>(rec + R::kKZero)[slot * 4 + g] = kq.zero;
+            for (int w = 0; w < words; ++w) store_once(&kc[((tile * words + w) * 16 + row) * 4 + g], kq.words[w]);
+            store_once(&reinterpret_cast<uint16_t *>(rec + R::kKScale)[slot * 4 + g], kq.scale);
+            store_once(&reinterpret_cast<uint16_t *>(rec + R::kKZero)[slot * 4 + g], kq.zero);
         }
 
         const GroupQ vq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(V + e));

@@ -7,9 +7,11 @@
 // mirror image of the append kernel, and loops over records with the next
 // record's loads already in flight.  Thread (slot = tid/4, part = tid%4) produces
 // channels 32*i + 8*part .. +7 of its token for the four groups i: one
-// 16-byte load fetches its K codes of all four groups, and each of its four
-// 16-byte stores per tensor completes a 64-byte line together with the three
-// neighbouring threads.  V is stored channel-major (a word holds several
+// 16-byte load fetches its K codes of all four groups.  Its four 16-byte
+// pieces of a row would each fill a quarter of a line; mirror-image threads of
+// two neighbouring slots trade pieces instead, so that eight lanes write one
+// whole 128-byte line per store instruction, and the stores are non-temporal
+// (the output is written once).  V is stored channel-major (a word holds several
 // tokens of one channel), so the V words are expanded into an LDS byte tile
 // first and each thread reads its token's codes back.
 //
@@ -56,6 +58,38 @@ __device__ __forceinline__ uint4 dequant8_each(uint32_t lo, uint32_t hi, const u
     return make_uint4(f(code_pair<0>(lo), sp[0], zp[0]), f(code_pair<2>(lo), sp[1], zp[1]),
                       f(code_pair<0>(hi), sp[2], zp[2]), f(code_pair<2>(hi), sp[3], zp[3]));
 }
+
+// Value of the lane that mirrors this one within its group of eight lanes (lane ^ 7).
+__device__ __forceinline__ uint32_t half_mirror(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);
+}
+__device__ __forceinline__ uint4 half_mirror(uint4 v)
+{
+    return make_uint4(half_mirror(v.x), half_mirror(v.y), half_mirror(v.z), half_mirror(v.w));
+}
+__device__ __forceinline__ uint4 pick(bool c, uint4 a, uint4 b) { return c ? a : b; }
+// Stores the four 16-byte pieces v[i] (channels 32 i + 8 part .. + 7) of this thread's token row so that every
+// store instruction of a wavefront writes whole 128-byte lines: thread (slot, part) and thread (slot ^ 1, 3 - part),
+// mirror images within eight lanes, trade one piece per line, and the eight lanes write first the line of the even
+// slot's row, then that of the odd slot's.
+__device__ __forceinline__ void store_row(uint16_t *__restrict__ out, int dst, bool valid, const uint4 (&v)[4], int slot, int part,
+                                          int head, int n_kv_heads)
+{
+    const bool odd = slot & 1;
+    const int dst_other = (int)half_mirror((uint32_t)dst);
+    const bool valid_other = half_mirror((uint32_t)valid) != 0;
+    uint4 *row_even = reinterpret_cast<uint4 *>(out + ((size_t)(odd ? dst_other : dst) * n_kv_heads + head) * kHeadDim);
+    uint4 *row_odd = reinterpret_cast<uint4 *>(out + ((size_t)(odd ? dst : dst_other) * n_kv_heads + head) * kHeadDim);
+    const bool valid_even = odd ? valid_other : valid, valid_odd = odd ? valid : valid_other;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint4 recv = half_mirror(pick(odd, v[2 * h], v[2 * h + 1]));
+        if (valid_even) store_once(row_even + 8 * h + (odd ? 7 - part : part), pick(odd, recv, v[2 * h]));
+        if (valid_odd) store_once(row_odd + 8 * h + (odd ? 4 + part : 3 - part), pick(odd, v[2 * h + 1], recv));
+    }
+}
+
 // Eight consecutive sub-byte codes starting at bit `shift` of w -> one code per byte.
 template <int BITS> __device__ __forceinline__ void spread8(uint32_t w, int shift, uint32_t &lo, uint32_t &hi)
 {
@@ -91,7 +125,8 @@ __device__ __forceinline__ void load_planes(Stage &st, const uint8_t *__restrict
     const uint4 *kc = reinterpret_cast<const uint4 *>(rec + R::kKCodes);
     // INT4: chunk (tile*4 + part)*16 + row = word `part` (8 channels) of the four groups
     // INT2: chunk (tile*2 + part/2)*16 + row = word part/2 (16 channels); this thread takes half part%2
-    st.kw = BITS == 4 ? kc[(tile * 4 + part) * 16 + row] : kc[(tile * 2 + (part >> 1)) * 16 + row];
+    // read once, and an instruction of a wavefront covers 1 KiB (INT4) or 512 B (INT2) of whole lines
+    st.kw = load_once(kc + (BITS == 4 ? (tile * 4 + part) * 16 + row : (tile * 2 + (part >> 1)) * 16 + row));
     if constexpr (KC) {
         if (tid < 64) st.km = reinterpret_cast<const uint4 *>(rec + R::kKScale)[tid];   // 512 B scale, 512 B zero
     } else {
@@ -175,23 +210,23 @@ __device__ __forceinline__ void gather_record(const Stage &st, uint16_t *__restr
 
     // ---- K: this thread's 8 channels of each group (per-token keys need nothing from LDS)
     const uint32_t w[4] = {st.kw.x, st.kw.y, st.kw.z, st.kw.w};
-    uint4 *kout = reinterpret_cast<uint4 *>(K_out + ((size_t)st.dst * n_kv_heads + head) * kHeadDim);
     if constexpr (!KC) {
-        if (valid) {
+        uint4 kv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t sc = i < 2 ? st.ksc.x : st.ksc.y, zc = i < 2 ? st.kzc.x : st.kzc.y;
-                const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc >> (16 * (i & 1))));
-                const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(zc >> (16 * (i & 1))));
-                uint32_t lo, hi;
-                spread8<BITS>(w[i], BITS == 4 ? 0 : 16 * (part & 1), lo, hi);
-                kout[4 * i + part] = dequant8(lo, hi, s, z);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t sc = i < 2 ? st.ksc.x : st.ksc.y, zc = i < 2 ? st.kzc.x : st.kzc.y;
+            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc >> (16 * (i & 1))));
+            const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(zc >> (16 * (i & 1))));
+            uint32_t lo, hi;
+            spread8<BITS>(w[i], BITS == 4 ? 0 : 16 * (part & 1), lo, hi);
+            kv[i] = dequant8(lo, hi, s, z);
         }
+        store_row(K_out, st.dst, valid, kv, slot, part, head, n_kv_heads);
     }
     __syncthreads();
     if constexpr (KC) {
-        if (valid) {
+        {
+            uint4 kv[4];
             // channels 32*i + 8*part + j: chunks (block, group i, quarter 2*(part/2) + j/4) of the planes, fp16
             // half part%2 of word j%4
             const uint4 *sp4 = lds.kmeta + (slot >> 5) * 16 + 2 * (part >> 1);
@@ -206,21 +241,23 @@ __device__ __forceinline__ void gather_record(const Stage &st, uint16_t *__restr
                                         __builtin_amdgcn_perm(z1.y, z1.x, sel), __builtin_amdgcn_perm(z1.w, z1.z, sel)};
                 uint32_t lo, hi;
                 spread8<BITS>(w[i], 16 * (part & 1), lo, hi);
-                kout[4 * i + part] = dequant8_each(lo, hi, sp, zp);
+                kv[i] = dequant8_each(lo, hi, sp, zp);
             }
+            store_row(K_out, st.dst, valid, kv, slot, part, head, n_kv_heads);
         }
     }
     // ---- V: codes from the byte tile, scale / zero from the staged planes
-    if (valid) {
-        uint4 *out = reinterpret_cast<uint4 *>(V_out + ((size_t)st.dst * n_kv_heads + head) * kHeadDim);
+    {
+        uint4 vv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int mi = vmeta_index(slot, i);
             const _Float16 s = __builtin_bit_cast(_Float16, lds.vmeta[mi]);
             const _Float16 z = __builtin_bit_cast(_Float16, lds.vmeta[kPageTokens * kGroups + mi]);
             const uint2 cb = *reinterpret_cast<const uint2 *>(&lds.codes[slot][32 * i + 8 * part]);
-            out[4 * i + part] = dequant8(cb.x, cb.y, s, z);
+            vv[i] = dequant8(cb.x, cb.y, s, z);
         }
+        store_row(V_out, st.dst, valid, vv, slot, part, head, n_kv_heads);
     }
 }
 
@@ -267,9 +304,8 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
                       int32_t *status, void *stream)
 {
     // A few looping workgroups per compute unit, fewer than would fit: the kernel is bound by the HBM write
-    // stream (82 % of its bytes are stores), and on MI355X that stream runs faster with fewer concurrent
-    // writers (cfg2, per-token keys: 339 / 283 / 298 / 316 / 344 us with 1 / 2 / 3 / 4 / 7 workgroups per
-    // unit; per-channel keys, which do more work per record: 448 / 371 / 328 / 330 / 346 with 1 .. 5).
+    // stream (82 % of its bytes are stores), and on MI355X that stream runs faster with few concurrent
+    // writers (cfg2, per-token keys: 271 / 243 / 243 / 249 us with 2 / 3 / 4 / 6 workgroups per unit).
     const bool kc = desc->int2_key_axis == TKV_KEYS_PER_CHANNEL;
     auto kernel = kc ? tkv_gather_kernel<true> : tkv_gather_kernel<false>;
     int dev = 0, cus = 0, per_cu = 0;
@@ -277,7 +313,7 @@ int tkv_launch_gather(const tkv_desc *desc, const void *pool, const uint8_t *bit
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu <= 0)
         return TKV_ERR_HIP;
-    const int wanted = kc ? 3 : 2;
+    const int wanted = 3;
     per_cu = per_cu < wanted ? per_cu : wanted;
     const int n_records = n_work * desc->n_kv_heads;
     const int n_blocks = n_records < cus * per_cu ? n_records : cus * per_cu;

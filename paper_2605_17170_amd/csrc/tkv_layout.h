@@ -63,5 +63,18 @@ __device__ __forceinline__ uint4 load_once(const uint4 *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// The counterpart for data that is written once and not read again by the same kernel.  Only where one store
+// instruction of a wavefront fills whole 128-byte lines (a plain 1 : 4 read : write stream of such stores runs at
+// 6.2 TB/s against 5.0 TB/s with ordinary ones); on lines filled by several instructions it is slower than an
+// ordinary store.
+__device__ __forceinline__ void store_once(uint4 *p, uint4 v)
+{
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t *>(p));
+}
+__device__ __forceinline__ void store_once(uint32_t *p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_once(uint16_t *p, uint16_t v) { __builtin_nontemporal_store(v, p); }
+
 } // namespace tkv
 #endif
