@@ -225,7 +225,7 @@ def append_leg(name, steps=5, warmup=2):
            "prefill_gather_ms": gms, "prefill_gather_GBps_read_plus_write": (wr + 2 * gK.numel() * 2) / (gms * 1e-3) / 1e9,
            "prefill_gather_frac_of_hbm_peak": frac(wr + 2 * gK.numel() * 2, gms),
            "stream_read4_write1_GBps": 5 * unit / (m41 * 1e-3) / 1e9, "stream_read1_write4_GBps": 5 * unit / (m14 * 1e-3) / 1e9,
-           "ceiling_note": "tkv_probe_stream_mix: plain 128-bit streams of the same size in the byte ratio of the append "
+           "ceiling_note": "tkv_probe_stream_mix: plain 128-bit streams (ordinary loads, non-temporal stores) of the same size in the byte ratio of the append "
                            "(reads 4, writes 1) and of the gather (reads 1, writes 4); the second one overwrites the pool, "
                            "after the measurements that needed it"}
     cache.close()
@@ -257,7 +257,7 @@ def main():
     n_layers = 80 if head == "cfg5" else 1
     main_res, (w, cache, pools, qs, out, ws) = decode_leg(head, steps, warmup, n_layers=n_layers)
 
-    # speed-of-light probe: a plain 128-bit streaming read of the same pools, same order
+    # speed-of-light probe: a plain 128-bit (non-temporal) streaming read of the same pools, same order
     probe, _ = timed(lambda i: tkv.tkv_probe_stream_read(pools[i % len(pools)]), 40, 5)
     stream_read = cache.pool_bytes / (float(np.mean(probe)) * 1e-3) / 1e9
     kv_layer, kv_step = main_res["kv_bytes_per_layer"], main_res["kv_bytes_per_step"]
@@ -295,7 +295,7 @@ def main():
                              "interval per launch from HIP events around the timed launches on the launch stream; algorithmic bytes "
                              "per launch = 96 B/INT2 token + 160 B/INT4 token per kv head of one layer; traffic = HBM bytes per launch "
                              "from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), null unless that summary was taken from these kernel "
-                             "sources; stream_read_GBps = a plain 128-bit streaming read of the same pools (tkv_probe_stream_read); "
+                             "sources; stream_read_GBps = a plain 128-bit streaming read of the same pools with non-temporal loads, as the kernel uses (tkv_probe_stream_read); "
                              "record_read_GBps = the pool's records read whole, one per wavefront at a time, addresses computed; "
                              "memory_skeleton = the same reads through the items and page tables, i.e. the decode kernel without "
                              "its arithmetic (tkv_probe_decode_reads, walk = 0 / 1)"},

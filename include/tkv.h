@@ -426,7 +426,8 @@ int tkv_decode_attention_static(const tkv_desc *desc, const void *pool, const ui
 /* ------------------------------------------------------------------ */
 /*
  * Streams `bytes` (a multiple of 16) of the device buffer `buf` (16-byte
- * aligned) through the GPU with 128-bit loads and discards them: the
+ * aligned) through the GPU with 128-bit non-temporal loads (the kind the
+ * kernels use for the records of the cache) and discards them: the
  * read-bandwidth ceiling of the device for a scan such as the decode kernel's
  * pass over the pool.  For benchmarks that report a kernel against what the
  * memory system delivers as well as against the published peak; it computes
@@ -456,7 +457,8 @@ int tkv_probe_decode_reads(const tkv_desc *desc, const void *pool, const int32_t
 /*
  * Streams read_parts * unit_bytes out of `src` and writes write_parts *
  * unit_bytes into `dst` (device, 16-byte aligned, unit_bytes a multiple of 16)
- * with 128-bit accesses: the ceiling of the device for a kernel that reads and
+ * with 128-bit accesses (ordinary loads, non-temporal stores: the fastest
+ * combination): the ceiling of the device for a kernel that reads and
  * writes in that byte ratio.  Supported ratios: 4 : 1 (tkv_quantize_append reads
  * 512 B of bf16 per 96..160 B it writes), 1 : 4 (tkv_gather_dequant), 1 : 1.
  * What is written is a fold of what was read.  unit_bytes = 0 is a no-op.
