@@ -9,7 +9,9 @@
 // group is 64 contiguous bytes of the input, so min/max need no cross-lane
 // step.  K words go straight to HBM (a wavefront's stores for one word index
 // are 256 contiguous bytes, written with non-temporal stores).  V codes are transposed through LDS, because
-// the V plane packs tokens, not channels, into a word.
+// the V plane packs tokens, not channels, into a word; for a page that arrives whole, the V words and the two V
+// metadata planes, which are adjacent in the record, are put together in LDS and leave in 16-byte non-temporal
+// stores, one KiB per instruction of a wavefront.
 //
 // Arithmetic is IEEE binary32 without fused multiply-add so that the codes,
 // scales and zero-points match a scalar CPU evaluation bit for bit:
@@ -120,12 +122,13 @@ struct NoLds {};
 template <int BITS, bool KC, class KL>
 __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, const uint16_t *V, int src,
                                               bool valid, int head, int n_kv_heads,
-                                              uint32_t (*lds_codes)[32], uint8_t *lds_valid, KL &kl)
+                                              uint32_t (*lds_codes)[32], uint8_t *lds_valid, uint4 *lds_vout, KL &kl)
 {
     using R = Rec<BITS>;
     const int tid = threadIdx.x, slot = tid >> 2, g = tid & 3;
     const int tile = slot >> 4, row = slot & 15;
     if (g == 0) lds_valid[slot] = valid;
+    uint16_t v_scale = 0, v_zero = 0;
     if (valid) {
         const size_t e = ((size_t)src * n_kv_heads + head) * kHeadDim + g * kGroup;
         if constexpr (KC) {
@@ -147,8 +150,12 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
 
         const GroupQ vq = quantize_group<BITS>(reinterpret_cast<const uint4 *>(V + e));
         const int mi = vmeta_index(slot, g);
-        reinterpret_cast<uint16_t *>(rec + R::kVScale)[mi] = vq.scale;
-        reinterpret_cast<uint16_t *>(rec + R::kVZero)[mi] = vq.zero;
+        v_scale = vq.scale;
+        v_zero = vq.zero;
+        // the two V metadata planes (2 x 512 B) are put together behind the V words in the staging area
+        uint16_t *meta = reinterpret_cast<uint16_t *>(lds_vout + R::kCodeBytes / 16);
+        meta[mi] = vq.scale;
+        meta[kMetaBytes / 2 + mi] = vq.zero;
         uint4 *dst = reinterpret_cast<uint4 *>(&lds_codes[slot][g * 8]);
         dst[0] = make_uint4(vq.bytes[0], vq.bytes[1], vq.bytes[2], vq.bytes[3]);
         dst[1] = make_uint4(vq.bytes[4], vq.bytes[5], vq.bytes[6], vq.bytes[7]);
@@ -231,10 +238,23 @@ __device__ __forceinline__ void append_record(uint8_t *rec, const uint16_t *K, c
             const uint32_t wv[4] = {__builtin_amdgcn_perm(t23, t01, 0x05040100u), __builtin_amdgcn_perm(t23, t01, 0x07060302u),
                                     __builtin_amdgcn_perm(u23, u01, 0x05040100u), __builtin_amdgcn_perm(u23, u01, 0x07060302u)};
             const int base = (((BITS == 4 ? blk * 2 : 0) + h) * 4 + quad) * 64;
+            uint32_t *vs = reinterpret_cast<uint32_t *>(lds_vout);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) vc[base + (4 * n4 + i) * 4 + k] = wv[i];
+            for (int i = 0; i < 4; ++i) vs[base + (4 * n4 + i) * 4 + k] = wv[i];
         }
+        __syncthreads();
+        // The V words and the two V metadata planes are adjacent in the record: one run of 16-byte stores,
+        // every instruction of a wavefront a whole KiB, written once
+        constexpr int n_chunks = (R::kCodeBytes + 2 * kMetaBytes) / 16;   // 192 (INT2) / 320 (INT4)
+        uint4 *dst = reinterpret_cast<uint4 *>(rec + R::kVCodes);
+#pragma unroll
+        for (int c = tid; c < n_chunks; c += 256) store_once(dst + c, lds_vout[c]);
         return;
+    }
+    if (valid) {
+        const int mi = vmeta_index(slot, g);
+        reinterpret_cast<uint16_t *>(rec + R::kVScale)[mi] = v_scale;
+        reinterpret_cast<uint16_t *>(rec + R::kVZero)[mi] = v_zero;
     }
 #pragma unroll
     for (int widx = tid; widx < n_words; widx += 256) {
@@ -272,6 +292,8 @@ __global__ __launch_bounds__(256) void tkv_append_kernel(
 {
     __shared__ __attribute__((aligned(16))) uint32_t lds_codes[kPageTokens][32];
     __shared__ uint8_t lds_valid[kPageTokens];
+    // a whole page's V words and V metadata planes in record order, on their way to 16-byte stores
+    __shared__ uint4 lds_vout[(Rec<4>::kCodeBytes + 2 * kMetaBytes) / 16];
     __shared__ typename std::conditional<KC, KcLds, NoLds>::type kl;
     const int w = blockIdx.x / n_kv_heads, head = blockIdx.x % n_kv_heads;
     const int page = work_pages[w];
@@ -300,13 +322,13 @@ __global__ __launch_bounds__(256) void tkv_append_kernel(
                 valid = false;
                 if (status && (threadIdx.x & 127) == 0) atomicOr(status, TKV_STATUS_BLOCK_PARTIAL);
             }
-            append_record<2, true>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+            append_record<2, true>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, lds_vout, kl);
         } else {
-            append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+            append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, lds_vout, kl);
         }
     } else {
-        if (bits == 2) append_record<2, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
-        else append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, kl);
+        if (bits == 2) append_record<2, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, lds_vout, kl);
+        else append_record<4, false>(rec, K, V, src, valid, head, n_kv_heads, lds_codes, lds_valid, lds_vout, kl);
     }
     if (head == 0 && __syncthreads_or(valid) && threadIdx.x == 0) bit_map[page] = (uint8_t)bits;
 }

@@ -79,9 +79,11 @@ __device__ __forceinline__ void store_row(uint16_t *__restrict__ out, int dst, b
     const bool odd = slot & 1;
     const int dst_other = (int)half_mirror((uint32_t)dst);
     const bool valid_other = half_mirror((uint32_t)valid) != 0;
-    uint4 *row_even = reinterpret_cast<uint4 *>(out + ((size_t)(odd ? dst_other : dst) * n_kv_heads + head) * kHeadDim);
-    uint4 *row_odd = reinterpret_cast<uint4 *>(out + ((size_t)(odd ? dst : dst_other) * n_kv_heads + head) * kHeadDim);
     const bool valid_even = odd ? valid_other : valid, valid_odd = odd ? valid : valid_other;
+    // (a row that is not written gets the address of row 0: no pointer is formed from an index that was never checked)
+    const size_t dst_even = valid_even ? (size_t)(odd ? dst_other : dst) : 0, dst_odd = valid_odd ? (size_t)(odd ? dst : dst_other) : 0;
+    uint4 *row_even = reinterpret_cast<uint4 *>(out + (dst_even * n_kv_heads + head) * kHeadDim);
+    uint4 *row_odd = reinterpret_cast<uint4 *>(out + (dst_odd * n_kv_heads + head) * kHeadDim);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const uint4 recv = half_mirror(pick(odd, v[2 * h], v[2 * h + 1]));
