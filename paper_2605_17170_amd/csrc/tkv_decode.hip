@@ -1018,7 +1018,9 @@ __global__ __launch_bounds__(TH) void tkv_reduce_rows_kernel(
     for (int i = i0 + slot; i < i1; i += kSlots) {
         const size_t ph = (size_t)i * n_q_heads + h;
         const float2 ml = reinterpret_cast<const float2 *>(ml_ws)[ph];
-        const float4 a = reinterpret_cast<const float4 *>(acc_ws + ph * kHeadDim)[cq];
+        // a partial is read once, 512 contiguous bytes per item
+        const uint4 au = load_once(reinterpret_cast<const uint4 *>(acc_ws + ph * kHeadDim) + cq);
+        const float4 a = make_float4(__uint_as_float(au.x), __uint_as_float(au.y), __uint_as_float(au.z), __uint_as_float(au.w));
         // an item without tokens has m = -inf, l = 0 and weighs nothing; no branch, so the loads of several
         // rounds are in flight together
         const float Mn = fmaxf(M, ml.x);
