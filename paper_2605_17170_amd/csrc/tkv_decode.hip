@@ -123,16 +123,16 @@ __device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c)
 // The value of the lane eight columns on in the same row of 16 lanes.
 __device__ __forceinline__ float row_ror8(float v)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, true));
 }
 __device__ __forceinline__ uint32_t ror8_u32(uint32_t v)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, true);
 }
 // The value of another lane of the same row of 16 lanes: CTRL is a DPP pattern under which every lane has a source.
 template <int CTRL> __device__ __forceinline__ float row_dpp(float v)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 // Sum / maximum over a row of 16 lanes, in every lane of the row: neighbours, pairs, quads, halves
 // (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror).
@@ -376,7 +376,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     const bool partial = n_valid < kPageTokens;   // wave-uniform: only the last page of a width can be partly filled
 
     // ---- stage metadata in LDS --------------------------------------------
-    uint2 kzv[2] = {{0u, 0u}, {0u, 0u}};   // K zeros of this lane's MFMA row per 32-token block (two token sets)
+    uint4 kzv[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};   // K zeros of this lane's MFMA row per 32-token block (two token sets), twice
     (void)kzv;
     {
         uint2 vsc = pr.vsc, vzc = pr.vzc;
@@ -407,10 +407,10 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
             // one group with one 16-byte read
             {
                 float *kst = lds.ks + (lane >> 5) * 128 + (lane & 31);
-                kst[0] = (float)a[0] * lc.F;
-                kst[32] = (float)a[1] * lc.F;
-                kst[64] = (float)b[0] * lc.F;
-                kst[96] = (float)b[1] * lc.F;
+                kst[0] = fmaf((float)a[0], lc.F, 0.0f);   // (one mixed-precision FMA converts and scales)
+                kst[32] = fmaf((float)a[1], lc.F, 0.0f);
+                kst[64] = fmaf((float)b[0], lc.F, 0.0f);
+                kst[96] = fmaf((float)b[1], lc.F, 0.0f);
             }
             // K zeros: lane (r, q4) takes those of token 32*blk + 16*(q4 >> 1) + r, which lane number that token holds.
             // An MFMA row holds a token of either set: a never-written token's zero-point (any bit pattern) would
@@ -419,7 +419,9 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
                 const int src = 4 * (32 * blk + 16 * (q4 >> 1) + r16);
-                kzv[blk] = make_uint2((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
+                kzv[blk] = make_uint4((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
+                                      (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.y),
+                                      (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
                                       (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.y));
             }
         }
@@ -499,7 +501,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         floatx4 s[2];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].x, kzv[blk].y);
+            const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].z, kzv[blk].w);
             s[blk] = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
         }
         // group by group, both 32-token blocks against one read of the q operand: two independent MFMA chains
