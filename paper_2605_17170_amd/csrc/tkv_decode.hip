@@ -120,7 +120,8 @@ __device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
-// The value of the lane eight columns on in the same row of 16 lanes.
+// The value of the lane eight columns on in the same row of 16 lanes.  (In all DPP moves here every lane has a source;
+// `bound_ctrl` says so to the compiler, which otherwise presets the destination register with a move of its own.)
 __device__ __forceinline__ float row_ror8(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, true));
@@ -376,7 +377,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
     const bool partial = n_valid < kPageTokens;   // wave-uniform: only the last page of a width can be partly filled
 
     // ---- stage metadata in LDS --------------------------------------------
-    uint4 kzv[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};   // K zeros of this lane's MFMA row per 32-token block (two token sets), twice
+    uint2 kzv[2] = {{0u, 0u}, {0u, 0u}};   // K zeros of this lane's MFMA row per 32-token block (two token sets)
     (void)kzv;
     {
         uint2 vsc = pr.vsc, vzc = pr.vzc;
@@ -419,9 +420,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
                 const int src = 4 * (32 * blk + 16 * (q4 >> 1) + r16);
-                kzv[blk] = make_uint4((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
-                                      (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.y),
-                                      (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
+                kzv[blk] = make_uint2((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.x),
                                       (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kzm.y));
             }
         }
@@ -501,7 +500,7 @@ __device__ __forceinline__ void compute_page(const PageRegs<BITS> &pr, int n_val
         floatx4 s[2];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].z, kzv[blk].w);
+            const half8 za = as_half8(kzv[blk].x, kzv[blk].y, kzv[blk].x, kzv[blk].y);
             s[blk] = mfma(za, qz, floatx4{0.f, 0.f, 0.f, 0.f});   // zero-point term
         }
         // group by group, both 32-token blocks against one read of the q operand: two independent MFMA chains
