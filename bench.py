@@ -73,21 +73,30 @@ def read_traffic(name):
 
 
 def timed(fn, steps, warmup):
-    """Runs fn(i) `warmup` + `steps` times; returns (per-step ms from HIP events on the launch stream, wall ms per
-    step between two synchronisations)."""
+    """Runs fn(i) at least `warmup` times untimed, then `steps` times; returns (ms per step from one pair of HIP events on the launch stream
+    around the `steps` timed calls, as an array of one element; wall ms per step between two synchronisations).
+    Nothing is recorded between the steps: an event per step costs 3-10 us of stream time each, which a step of
+    tens of microseconds would carry as if it were its own."""
     import torch
-    for i in range(warmup):
-        fn(i)
+    # untimed: `warmup` calls, and more of them until the device has been busy for 30 ms (a short warm-up leaves
+    # the clocks low: the first 12 ms of cfg2 steps after 1 ms of warm-up run 20 % slower than the next 12 ms)
+    t_warm = time.perf_counter()
+    n_warm = 0
+    while n_warm < warmup or (time.perf_counter() - t_warm < 0.030 and n_warm < 100000):
+        fn(n_warm)
+        n_warm += 1
+        if n_warm % 64 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    ev[0].record()
+    first.record()
     for i in range(steps):
         fn(i)
-        ev[i + 1].record()
+    last.record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3 / steps
-    return np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]), wall
+    return np.array([first.elapsed_time(last) / steps]), wall
 
 
 def frac(nbytes, ms):
